@@ -1,0 +1,147 @@
+/*
+ * dmoe.h -- C ABI of the MI355X (gfx950) dropless-MoE expert layer.
+ *
+ * The layer is the dMoE of "MegaBlocks: Efficient Sparse Training with Mixture-of-Experts" (arXiv 2211.15841),
+ * Figure 6:   router -> make_topology -> padded_gather -> sdd -> dsd -> padded_scatter -> scale,
+ * with the backward products of Section 5.1 (SDD^T, DS^TD, DSD^T, DD^TS).
+ *
+ * Problem statement (Figure 6, Section 2.1):
+ *   x        [T, d]      tokens, row-major bf16                      T = num_tokens, d = d_model (hidden_size)
+ *   w_router [d, E]      router projection, row-major bf16           E = num_experts
+ *   w1       [d, E*h]    first expert layer, row-major bf16          h = ffn_hidden; expert e owns columns [e*h,(e+1)*h)
+ *   w2       [E*h, d]    second expert layer, row-major bf16         expert e owns rows [e*h,(e+1)*h)
+ *   y        [T, d]      layer output, row-major bf16
+ * All matrix products accumulate in fp32.  "bf16" means the upper 16 bits of an IEEE binary32.
+ *
+ * Conventions
+ *   - Every pointer named below is a DEVICE pointer into caller-owned memory unless it says "host".
+ *     The library allocates no device memory, frees none, and keeps no device state between calls.
+ *   - Every device buffer must be 256-byte aligned.  Outputs are overwritten (never accumulated into).
+ *   - dmoe_topology / dmoe_forward / dmoe_backward only enqueue work on `stream` (a hipStream_t passed as
+ *     void*; NULL = the null stream).  They never synchronise and never copy to the host: the padded row
+ *     count P and the number of nonzero blocks live in device memory (dmoe_topology_t.counts) and the
+ *     kernels read them there, so buffers are sized for the upper bounds reported by dmoe_sizes().
+ *   - Return value: DMOE_OK (0) or a negative error code; dmoe_last_error() gives a message.  Arguments are
+ *     validated on the host before anything is launched; on error nothing has been enqueued.
+ *   - Inputs holding NaN or infinity give undefined routing.
+ */
+#ifndef DMOE_H_
+#define DMOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define DMOE_API __attribute__((visibility("default")))
+#else
+#define DMOE_API
+#endif
+
+#define DMOE_OK        0
+#define DMOE_EINVAL   (-1)   /* null pointer, misaligned pointer, or a configuration outside the supported set */
+#define DMOE_ENOMEM   (-2)   /* a caller-provided buffer is smaller than dmoe_sizes() asks for                  */
+#define DMOE_ELAUNCH  (-3)   /* the HIP runtime reported an error while enqueueing                              */
+
+#define DMOE_BLOCK 128       /* side of a sparse block (Section 5.1.2: 128x128 blocks)                          */
+
+/* Layer hyper-parameters.  Supported: block == 128; d_model and ffn_hidden multiples of 128;
+ * 1 <= top_k <= min(num_experts, 8); 1 <= num_experts <= 256; num_tokens >= 1; num_tokens*top_k < 2^24. */
+typedef struct {
+  int32_t num_tokens;      /* T */
+  int32_t d_model;         /* d  (hidden_size)     */
+  int32_t ffn_hidden;      /* h  (ffn_hidden_size) */
+  int32_t num_experts;     /* E */
+  int32_t top_k;           /* k  experts per token (Section 2.1) */
+  int32_t block;           /* must be 128 */
+  int32_t activation;      /* 0: exact GELU  v*Phi(v)  between the two expert layers */
+  int32_t normalize_topk;  /* 0: confidence = softmax probability of the chosen expert (Section 2.1);
+                              1: that, divided by the sum over the token's k chosen experts */
+} dmoe_config;
+
+/* Routing result + block-sparse topology, all in device memory (views into one caller-owned allocation,
+ * laid out by dmoe_topology_bind).  f = t*top_k + s is the flat index of token t's s-th choice.
+ * Index arrays are block-wise int32 (Figure 5).  With R = P/128 block-rows, hb = h/128, nnz = R*hb:           */
+typedef struct {
+  int32_t *expert_idx;         /* [T*k]     chosen expert of f; slots in descending score, ties -> lower expert */
+  float   *weights;            /* [T*k]     confidence of f (fp32)                                               */
+  float   *logits;             /* [T*E]     router scores (fp32, bias included), kept for the backward pass      */
+  int32_t *tokens_per_expert;  /* [E]       n_e                                                                  */
+  int32_t *padded_offsets;     /* [E+1]     first padded row of each expert; rows per expert = ceil(n_e/128)*128 */
+  int32_t *row_of;             /* [T*k]     padded row holding f (stable: ascending f inside an expert)          */
+  int32_t *token_of;           /* [P_max]   f held by a padded row, -1 on padding rows (valid for rows < P)      */
+  int32_t *row_offsets;        /* [R_max+1] blocked CSR: first block of each block-row            (Sec. 5.1.3)   */
+  int32_t *column_indices;     /* [nnz_max] blocked CSR: block-column of each block, row-wise order              */
+  int32_t *row_indices;        /* [nnz_max] block-row of each block (the COO half of the hybrid encoding)        */
+  int32_t *column_offsets_t;   /* [E*hb+1]  transposed matrix: first entry of each block-column   (Sec. 5.1.4)   */
+  int32_t *row_indices_t;      /* [nnz_max] transposed order: block-row of each entry, ascending in a column     */
+  int32_t *block_offsets_t;    /* [nnz_max] transposed order: number of that block in the primary order          */
+  int32_t *counts;             /* [4]       P, R, nnz, 0                                                         */
+  int32_t *expert_order;       /* [E]       experts by descending n_e (ties -> lower expert); schedules the
+                                            weight-gradient products heaviest first                              */
+} dmoe_topology_t;
+
+/* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,
+ * nnz_max = (P_max/128)*(h/128).  topology: the arrays of dmoe_topology_t; saved: what forward keeps for
+ * backward (permuted tokens, both sparse activations, permuted expert output); scratch: the larger of what
+ * the three calls need (contents are dead after each call returns... after its work completes).             */
+DMOE_API int dmoe_sizes(const dmoe_config *cfg, size_t *topology_bytes, size_t *saved_bytes, size_t *scratch_bytes,
+               int32_t *P_max, int32_t *nnz_max);
+
+/* Carve `topology_mem` (device, `bytes` >= topology_bytes) into the arrays of *out (host struct).  No GPU work. */
+DMOE_API int dmoe_topology_bind(const dmoe_config *cfg, void *topology_mem, size_t bytes, dmoe_topology_t *out);
+
+/* Steps (1)-(2) of Figure 6: route every token (Section 2.1), group the assignments by expert with each
+ * group padded to a multiple of 128 rows (Section 5.2), and build the blocked-CSR-COO topology with its
+ * transpose indices (Sections 5.1.3, 5.1.4).  router_bias: fp32 [E] added to the scores, or NULL.
+ * Router scores are accumulated in fp32 in ascending hidden index, so expert_idx is reproducible bit for bit. */
+DMOE_API int dmoe_topology(const dmoe_config *cfg, const void *x, const void *w_router, const float *router_bias,
+                  dmoe_topology_t *topo, void *scratch, size_t scratch_bytes, void *stream);
+
+/* Steps (3)-(5) of Figure 6: padded gather, SDD (+GELU), DSD, padded scatter scaled by the confidences and
+ * summed over the k slots (Section 2.4).  Writes y [T,d] bf16 and `saved` (>= saved_bytes).                    */
+DMOE_API int dmoe_forward(const dmoe_config *cfg, const void *x, const void *w1, const void *w2,
+                 const dmoe_topology_t *topo, void *y, void *saved, size_t saved_bytes,
+                 void *scratch, size_t scratch_bytes, void *stream);
+
+/* Backward of the layer for upstream gradient dy [T,d] bf16 (Section 5.1: SDD^T and DS^TD for the second
+ * layer, DSD^T and DD^TS for the first), plus the router's gradient with the assignments held constant.
+ * Writes dx [T,d] bf16, dw_router [d,E] fp32, dw1 [d,E*h] bf16, dw2 [E*h,d] bf16; the slices of dw1/dw2 that
+ * belong to experts with no tokens are written as zeros.                                                      */
+DMOE_API int dmoe_backward(const dmoe_config *cfg, const void *x, const void *w_router, const void *w1, const void *w2,
+                  const dmoe_topology_t *topo, const void *saved, size_t saved_bytes, const void *dy,
+                  void *dx, void *dw_router, void *dw1, void *dw2,
+                  void *scratch, size_t scratch_bytes, void *stream);
+
+/* Test helper: waits for `stream` and copies counts[4] (P, R, nnz, 0) to host memory `out4`. */
+DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out4, void *stream);
+
+/* Timing helper for benchmarks: when `events` (host array of 2*DMOE_NUM_STAGES hipEvent_t, created by the
+ * caller) is non-NULL, the next calls on this thread record an event before and after each stage's kernels
+ * on the stream they are launched on.  Pass NULL to switch it off.  Stage numbers are DMOE_STAGE_*.           */
+#define DMOE_STAGE_ROUTER        0   /* scores, top-k, softmax                        (dmoe_topology) */
+#define DMOE_STAGE_SORT          1   /* histogram, offsets, stable ranks              (dmoe_topology) */
+#define DMOE_STAGE_TOPOLOGY      2   /* blocked-CSR-COO arrays and transpose indices  (dmoe_topology) */
+#define DMOE_STAGE_GATHER        3   /* padded gather                                 (dmoe_forward)  */
+#define DMOE_STAGE_SDD           4   /* H = Xp W1, A = gelu(H)                        (dmoe_forward)  */
+#define DMOE_STAGE_DSD           5   /* Yp = A W2                                     (dmoe_forward)  */
+#define DMOE_STAGE_SCATTER       6   /* weighted un-permute                           (dmoe_forward)  */
+#define DMOE_STAGE_BWD_GATHER    7   /* dYp = w dY permuted, dweights                 (dmoe_backward) */
+#define DMOE_STAGE_SDDT          8   /* dA = dYp W2^T, dH = dA gelu'(H)               (dmoe_backward) */
+#define DMOE_STAGE_DSTD          9   /* dW2 = A^T dYp                                 (dmoe_backward) */
+#define DMOE_STAGE_DSDT         10   /* dXp = dH W1^T                                 (dmoe_backward) */
+#define DMOE_STAGE_DDTS         11   /* dW1 = Xp^T dH                                 (dmoe_backward) */
+#define DMOE_STAGE_ROUTER_BWD   12   /* dlogits, dW_r, un-permute of dXp + router term (dmoe_backward) */
+#define DMOE_NUM_STAGES         13
+DMOE_API int dmoe_set_stage_events(void *events);
+
+/* Message for the last error returned on this thread (host pointer to static thread-local storage). */
+DMOE_API const char *dmoe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMOE_H_ */

@@ -1,0 +1,11 @@
+"""MI355X-native dropless-MoE (dMoE) expert layer: thin Python binding over the C-ABI library libdmoe.so.
+
+Every step of the layer runs in the hand-written HIP kernels of csrc/; Python only marshals arguments and
+uses torch for device memory and the stream handle.  There is no CPU or eager fallback: importing the
+binding without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    DMoEConfig, DMoETopology, Workspace, load_library, dmoe_sizes, dmoe_topology_bind, dmoe_topology,
+    dmoe_forward, dmoe_backward, dmoe_topology_counts_host, dmoe_set_stage_events, dmoe_last_error,
+    STAGE_NAMES, DMoEError,
+)

@@ -1,0 +1,201 @@
+"""ctypes binding of include/dmoe.h.  Same names as the C entry points; argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_int32, c_size_t, c_void_p, c_char_p, POINTER, byref
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdmoe.so")
+
+STAGE_NAMES = ["router", "sort", "topology", "gather", "sdd", "dsd", "scatter", "bwd_gather", "sddt", "dstd",
+               "dsdt", "ddts", "router_bwd"]
+
+
+class DMoEError(RuntimeError):
+    pass
+
+
+class DMoEConfig(ctypes.Structure):
+    _fields_ = [("num_tokens", c_int32), ("d_model", c_int32), ("ffn_hidden", c_int32), ("num_experts", c_int32),
+                ("top_k", c_int32), ("block", c_int32), ("activation", c_int32), ("normalize_topk", c_int32)]
+
+
+_TOPO_FIELDS = ["expert_idx", "weights", "logits", "tokens_per_expert", "padded_offsets", "row_of", "token_of",
+                "row_offsets", "column_indices", "row_indices", "column_offsets_t", "row_indices_t",
+                "block_offsets_t", "counts", "expert_order"]
+
+
+class DMoETopology(ctypes.Structure):
+    _fields_ = [(n, c_void_p) for n in _TOPO_FIELDS]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdmoe.so (built in-tree by paper_2211_15841_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise DMoEError("libdmoe.so is not built: run `python -m paper_2211_15841_amd.build` "
+                        "(or __graft_entry__.build()); there is no fallback path")
+    # torch ships its own HIP runtime; make sure that one is the copy already resident so that stream handles
+    # and device pointers created by torch are valid inside the library.
+    hip_rt = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(hip_rt):
+        ctypes.CDLL(hip_rt, mode=ctypes.RTLD_GLOBAL)
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.dmoe_sizes.argtypes = [POINTER(DMoEConfig), POINTER(c_size_t), POINTER(c_size_t), POINTER(c_size_t),
+                               POINTER(c_int32), POINTER(c_int32)]
+    lib.dmoe_topology_bind.argtypes = [POINTER(DMoEConfig), c_void_p, c_size_t, POINTER(DMoETopology)]
+    lib.dmoe_topology.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, POINTER(DMoETopology), c_void_p,
+                                  c_size_t, c_void_p]
+    lib.dmoe_forward.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, POINTER(DMoETopology), c_void_p,
+                                 c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
+    lib.dmoe_backward.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, c_void_p, POINTER(DMoETopology),
+                                  c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                  c_size_t, c_void_p]
+    lib.dmoe_topology_counts_host.argtypes = [POINTER(DMoETopology), POINTER(c_int32), c_void_p]
+    lib.dmoe_set_stage_events.argtypes = [c_void_p]
+    lib.dmoe_last_error.restype = c_char_p
+    for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
+                 "dmoe_topology_counts_host", "dmoe_set_stage_events"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def dmoe_last_error() -> str:
+    return load_library().dmoe_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise DMoEError("dmoe error %d: %s" % (rc, dmoe_last_error()))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def dmoe_sizes(cfg: DMoEConfig) -> dict:
+    tb, sb, wb = c_size_t(), c_size_t(), c_size_t()
+    pm, nm = c_int32(), c_int32()
+    _check(load_library().dmoe_sizes(byref(cfg), byref(tb), byref(sb), byref(wb), byref(pm), byref(nm)))
+    return {"topology_bytes": tb.value, "saved_bytes": sb.value, "scratch_bytes": wb.value, "P_max": pm.value,
+            "nnz_max": nm.value}
+
+
+def dmoe_topology_bind(cfg: DMoEConfig, topology_mem, nbytes: int) -> DMoETopology:
+    topo = DMoETopology()
+    _check(load_library().dmoe_topology_bind(byref(cfg), _ptr(topology_mem), nbytes, byref(topo)))
+    return topo
+
+
+def dmoe_topology(cfg, x, w_router, router_bias, topo, scratch, scratch_bytes, stream=None):
+    _check(load_library().dmoe_topology(byref(cfg), _ptr(x), _ptr(w_router), _ptr(router_bias), byref(topo),
+                                        _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def dmoe_forward(cfg, x, w1, w2, topo, y, saved, saved_bytes, scratch, scratch_bytes, stream=None):
+    _check(load_library().dmoe_forward(byref(cfg), _ptr(x), _ptr(w1), _ptr(w2), byref(topo), _ptr(y), _ptr(saved),
+                                       saved_bytes, _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def dmoe_backward(cfg, x, w_router, w1, w2, topo, saved, saved_bytes, dy, dx, dw_router, dw1, dw2, scratch,
+                  scratch_bytes, stream=None):
+    _check(load_library().dmoe_backward(byref(cfg), _ptr(x), _ptr(w_router), _ptr(w1), _ptr(w2), byref(topo),
+                                        _ptr(saved), saved_bytes, _ptr(dy), _ptr(dx), _ptr(dw_router), _ptr(dw1),
+                                        _ptr(dw2), _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def dmoe_topology_counts_host(topo, stream=None):
+    out = (c_int32 * 4)()
+    _check(load_library().dmoe_topology_counts_host(byref(topo), out, _stream(stream)))
+    return list(out)
+
+
+def dmoe_set_stage_events(events_array):
+    """events_array: ctypes array of 2*len(STAGE_NAMES) hipEvent_t handles (0 = skip), or None."""
+    load_library().dmoe_set_stage_events(events_array)
+
+
+class Workspace:
+    """Caller-side buffers for one layer configuration, allocated once with torch (device memory only)."""
+
+    def __init__(self, num_tokens, d_model, ffn_hidden, num_experts, top_k, normalize_topk=0, device="cuda:0"):
+        self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, 0, normalize_topk)
+        self.device = torch.device(device)
+        self.sizes = dmoe_sizes(self.cfg)
+        u8 = dict(dtype=torch.uint8, device=self.device)
+        self.topology_mem = torch.empty(self.sizes["topology_bytes"], **u8)
+        self.saved = torch.empty(self.sizes["saved_bytes"], **u8)
+        self.scratch = torch.empty(self.sizes["scratch_bytes"], **u8)
+        self.topo = dmoe_topology_bind(self.cfg, self.topology_mem, self.sizes["topology_bytes"])
+        T, d, h, E = num_tokens, d_model, ffn_hidden, num_experts
+        bf = dict(dtype=torch.bfloat16, device=self.device)
+        self.y = torch.empty(T, d, **bf)
+        self.dx = torch.empty(T, d, **bf)
+        self.dw1 = torch.empty(d, E * h, **bf)
+        self.dw2 = torch.empty(E * h, d, **bf)
+        self.dw_router = torch.empty(d, E, dtype=torch.float32, device=self.device)
+
+    # -- the three calls of the layer ---------------------------------------------------------------------
+    def topology(self, x, w_router, router_bias=None, stream=None):
+        dmoe_topology(self.cfg, x, w_router, router_bias, self.topo, self.scratch, self.sizes["scratch_bytes"], stream)
+
+    def forward(self, x, w1, w2, stream=None):
+        dmoe_forward(self.cfg, x, w1, w2, self.topo, self.y, self.saved, self.sizes["saved_bytes"], self.scratch,
+                     self.sizes["scratch_bytes"], stream)
+        return self.y
+
+    def backward(self, x, w_router, w1, w2, dy, stream=None):
+        dmoe_backward(self.cfg, x, w_router, w1, w2, self.topo, self.saved, self.sizes["saved_bytes"], dy, self.dx,
+                      self.dw_router, self.dw1, self.dw2, self.scratch, self.sizes["scratch_bytes"], stream)
+        return self.dx, self.dw_router, self.dw1, self.dw2
+
+    # -- read-back of the topology arrays (tests) ----------------------------------------------------------
+    def topology_arrays(self) -> dict:
+        """Copies of the routing/topology arrays as CPU torch tensors, trimmed to their valid lengths."""
+        torch.cuda.synchronize(self.device)
+        c = self.cfg
+        F, E, hb = c.num_tokens * c.top_k, c.num_experts, c.ffn_hidden // 128
+        P, R, nnz, _ = dmoe_topology_counts_host(self.topo)
+        base = self.topology_mem.data_ptr()
+
+        def view(name, n, dtype):
+            off = getattr(self.topo, name) - base
+            return self.topology_mem[off:off + 4 * n].view(dtype).cpu()
+
+        i32, f32 = torch.int32, torch.float32
+        return {
+            "expert_idx": view("expert_idx", F, i32).reshape(c.num_tokens, c.top_k),
+            "weights": view("weights", F, f32).reshape(c.num_tokens, c.top_k),
+            "logits": view("logits", c.num_tokens * E, f32).reshape(c.num_tokens, E),
+            "tokens_per_expert": view("tokens_per_expert", E, i32),
+            "padded_offsets": view("padded_offsets", E + 1, i32),
+            "row_of": view("row_of", F, i32),
+            "token_of": view("token_of", P, i32),
+            "row_offsets": view("row_offsets", R + 1, i32),
+            "column_indices": view("column_indices", nnz, i32),
+            "row_indices": view("row_indices", nnz, i32),
+            "column_offsets_t": view("column_offsets_t", E * hb + 1, i32),
+            "row_indices_t": view("row_indices_t", nnz, i32),
+            "block_offsets_t": view("block_offsets_t", nnz, i32),
+            "counts": torch.tensor([P, R, nnz, 0], dtype=i32),
+            "expert_order": view("expert_order", E, i32),
+        }

@@ -1,0 +1,99 @@
+// Shared device/host helpers of the gfx950 dMoE library (internal; the public boundary is include/dmoe.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dmoe.h"
+
+namespace dmoe {
+
+typedef unsigned short bf16_t;                                        // raw bfloat16 bits in memory
+typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));
+typedef float f32x2_v __attribute__((ext_vector_type(2)));
+typedef float f32x4_v __attribute__((ext_vector_type(4)));
+typedef float f32x16_v __attribute__((ext_vector_type(16)));
+typedef short s16x4_v __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = DMOE_BLOCK;   // 128x128 sparse blocks (Section 5.1.2)
+constexpr int kMaxTopK = 8;
+constexpr int kMaxExperts = 256;
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Two fp32 -> packed bf16 pair (round to nearest even; one v_cvt_pk_bf16_f32 on gfx950). `lo` lands in bits 0..15.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2_v v = {lo, hi};
+  bf16x2_v b = __builtin_convertvector(v, bf16x2_v);
+  return *reinterpret_cast<uint32_t*>(&b);
+}
+
+// Standard normal CDF Phi(v) and density phi(v), fp32.  erfc through the five-term rational-exponential
+// approximation of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7), arranged so that the small tail is
+// computed directly rather than as 1 - (almost 1).
+__device__ __forceinline__ void normal_cdf_pdf(float v, float& cdf, float& pdf) {
+  const float az = fabsf(v) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(az, 0.3275911f, 1.0f));
+  float poly = fmaf(t, 1.061405429f, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  poly *= t;
+  const float ex = __expf(-0.5f * v * v);
+  const float tail = 0.5f * poly * ex;              // = Phi(-|v|)
+  cdf = v < 0.0f ? tail : 1.0f - tail;
+  pdf = ex * 0.39894228040143268f;
+}
+__device__ __forceinline__ float gelu_fwd(float v) {
+  float c, p;
+  normal_cdf_pdf(v, c, p);
+  return v * c;
+}
+__device__ __forceinline__ float gelu_bwd(float v) {   // d/dv [v Phi(v)] = Phi(v) + v phi(v)
+  float c, p;
+  normal_cdf_pdf(v, c, p);
+  return fmaf(v, p, c);
+}
+
+struct StageEvents {            // optional per-stage timing events (see dmoe_set_stage_events)
+  hipEvent_t* ev;
+  hipStream_t stream;
+  __host__ void begin(int stage) const { if (ev && ev[2 * stage]) (void)hipEventRecord(ev[2 * stage], stream); }
+  __host__ void end(int stage) const { if (ev && ev[2 * stage + 1]) (void)hipEventRecord(ev[2 * stage + 1], stream); }
+};
+
+// ---- launchers implemented in the .hip files (all enqueue on `s`, none synchronises) -------------------------
+struct Scratch;  // forward
+
+void launch_router(const dmoe_config& c, const bf16_t* x, const bf16_t* wr, const float* bias,
+                   const dmoe_topology_t& t, hipStream_t s);
+void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_counts, int p_max, hipStream_t s);
+void launch_make_topology(const dmoe_config& c, const dmoe_topology_t& t, int p_max, int nnz_max, hipStream_t s);
+
+void launch_padded_gather(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* x, bf16_t* xp, int p_max,
+                          hipStream_t s);
+void launch_weighted_scatter(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* yp, bf16_t* y,
+                             hipStream_t s);
+void launch_bwd_gather(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* dy, const bf16_t* yp,
+                       bf16_t* dyp, float* dweights, int p_max, hipStream_t s);
+void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* x, const bf16_t* wr,
+                       const float* dweights, const bf16_t* dxp, float* dlogits, float* partials, int num_partials,
+                       bf16_t* dx, float* dw_router, hipStream_t s);
+int router_bwd_num_partials(const dmoe_config& c);
+
+enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5 };
+struct BsArgs {
+  const dmoe_topology_t* topo;
+  int d, h, E, r_max, nnz_max;
+  const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
+  const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
+  const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: H for gelu')
+  bf16_t* out0;            // SDD: H blocks; SDDT: dH blocks; others: dense output
+  bf16_t* out1;            // SDD: A = gelu(H) blocks
+};
+void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s);
+
+}  // namespace dmoe

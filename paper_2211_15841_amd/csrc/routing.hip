@@ -1,0 +1,382 @@
+// Router, stable grouping by expert, and block-sparse topology construction (steps (1)-(2) of Figure 6).
+//
+//   router_logits_kernel  scores = x Wr (+ bias), fp32, accumulated in ascending hidden index  (Section 2.1)
+//   topk_kernel           greedy top-k on the scores, softmax confidences                      (Section 2.1)
+//   chunk_hist_kernel     per-chunk expert histogram (wave ballots)                            (Section 5.2)
+//   offsets_kernel        scan over chunks and experts: n_e, padded offsets, counts, expert order
+//   rank_kernel           stable destination row of every assignment, and its inverse
+//   topology_kernel       blocked CSR + per-block row indices + transpose indices              (Sections 5.1.3-5.1.4)
+#include "common.h"
+
+namespace dmoe {
+
+// ------------------------------------------------------------------------------------------------ scores
+// One lane owns one expert (of a chunk of EPAD experts) for TPT tokens; a wave holds 64/EPAD token groups.
+// The x tile is staged in LDS as fp32 and read as broadcasts, the Wr tile as fp32 rows.  Every (token, expert)
+// accumulator sees its products in ascending hidden index, one fused multiply-add each: a bf16 x bf16 product
+// is exact in fp32, so the sum is reproducible bit for bit by any implementation that keeps the order.
+constexpr int kRouterTPT = 4;
+constexpr int kRouterKT = 32;
+
+template <int EPAD>
+__global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
+                                                            const float* __restrict__ bias, float* __restrict__ logits,
+                                                            int T, int d, int E) {
+  constexpr int GW = 64 / EPAD;                 // token groups per wave
+  constexpr int TT = 4 * GW * kRouterTPT;       // tokens per workgroup
+  constexpr int XP = kRouterKT + 4;             // padded row of the x tile (floats)
+  __shared__ __attribute__((aligned(16))) float xs[TT * XP];
+  __shared__ __attribute__((aligned(16))) float ws[kRouterKT * EPAD];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int el = lane % EPAD;
+  const int group = wave * GW + lane / EPAD;
+  const int tile0 = blockIdx.x * TT;
+  const int tok_local = group * kRouterTPT;
+
+  for (int e0 = 0; e0 < E; e0 += EPAD) {
+    float acc[kRouterTPT];
+#pragma unroll
+    for (int j = 0; j < kRouterTPT; ++j) acc[j] = 0.0f;
+
+    for (int i0 = 0; i0 < d; i0 += kRouterKT) {
+      __syncthreads();
+      for (int q = tid; q < TT * (kRouterKT / 8); q += 256) {
+        const int tl = q / (kRouterKT / 8), c = q % (kRouterKT / 8);
+        const int t = tile0 + tl;
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (t < T) raw = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c * 8);
+        float4 lo = make_float4(bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y));
+        float4 hi = make_float4(bf16_lo(raw.z), bf16_hi(raw.z), bf16_lo(raw.w), bf16_hi(raw.w));
+        *reinterpret_cast<float4*>(&xs[tl * XP + c * 8]) = lo;
+        *reinterpret_cast<float4*>(&xs[tl * XP + c * 8 + 4]) = hi;
+      }
+      for (int q = tid; q < kRouterKT * EPAD; q += 256) {
+        const int i = q / EPAD, e = e0 + q % EPAD;
+        ws[q] = e < E ? bf16_to_f32(wr[(size_t)(i0 + i) * E + e]) : 0.0f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kRouterKT; i += 4) {
+        const float w0 = ws[(i + 0) * EPAD + el], w1 = ws[(i + 1) * EPAD + el];
+        const float w2 = ws[(i + 2) * EPAD + el], w3 = ws[(i + 3) * EPAD + el];
+#pragma unroll
+        for (int j = 0; j < kRouterTPT; ++j) {
+          const float4 xv = *reinterpret_cast<const float4*>(&xs[(tok_local + j) * XP + i]);
+          acc[j] = fmaf(xv.x, w0, acc[j]);
+          acc[j] = fmaf(xv.y, w1, acc[j]);
+          acc[j] = fmaf(xv.z, w2, acc[j]);
+          acc[j] = fmaf(xv.w, w3, acc[j]);
+        }
+      }
+    }
+    const int e = e0 + el;
+    if (e < E) {
+      const float b = bias ? bias[e] : 0.0f;
+#pragma unroll
+      for (int j = 0; j < kRouterTPT; ++j) {
+        const int t = tile0 + tok_local + j;
+        if (t < T) logits[(size_t)t * E + e] = bias ? acc[j] + b : acc[j];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ top-k
+// G lanes cooperate on one token.  Slot s takes the best score not taken yet (ties -> lower expert index);
+// confidences are softmax probabilities of the chosen experts (max-subtracted, fp32).
+template <int G>
+__global__ void __launch_bounds__(256) topk_kernel(const float* __restrict__ logits, int32_t* __restrict__ expert_idx,
+                                                   float* __restrict__ weights, int T, int E, int k, int normalize) {
+  const int tid = threadIdx.x;
+  const int sub = tid % G;
+  const int t = blockIdx.x * (256 / G) + tid / G;
+  const bool live = t < T;
+  const float* lg = logits + (size_t)(live ? t : 0) * E;
+
+  int sel[kMaxTopK];
+  float selv[kMaxTopK];
+#pragma unroll
+  for (int s = 0; s < kMaxTopK; ++s) { sel[s] = -1; selv[s] = 0.0f; }
+
+#pragma unroll
+  for (int s = 0; s < kMaxTopK; ++s) {
+    if (s < k) {
+      float bv = -INFINITY;
+      int bi = 0x7fffffff;
+      for (int e = sub; e < E; e += G) {
+        const float v = lg[e];
+        bool taken = false;
+#pragma unroll
+        for (int u = 0; u < kMaxTopK; ++u) taken |= (u < s) && (sel[u] == e);
+        if (!taken && (bi == 0x7fffffff || v > bv)) { bv = v; bi = e; }   // always lands on a valid expert
+      }
+#pragma unroll
+      for (int off = G / 2; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, G);
+        const int oi = __shfl_xor(bi, off, G);
+        if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+      }
+      sel[s] = bi;
+      selv[s] = bv;
+    }
+  }
+  const float m = selv[0];
+  float sum = 0.0f;
+  for (int e = sub; e < E; e += G) sum += __expf(lg[e] - m);
+#pragma unroll
+  for (int off = G / 2; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, G);
+  const float inv = 1.0f / sum;
+  float w[kMaxTopK];
+  float z = 0.0f;
+#pragma unroll
+  for (int s = 0; s < kMaxTopK; ++s) {
+    w[s] = (s < k) ? __expf(selv[s] - m) * inv : 0.0f;
+    z += w[s];
+  }
+  if (normalize) {
+    const float iz = 1.0f / z;
+#pragma unroll
+    for (int s = 0; s < kMaxTopK; ++s) w[s] *= iz;
+  }
+  if (live && sub == 0) {
+#pragma unroll
+    for (int s = 0; s < kMaxTopK; ++s) {
+      if (s < k) {
+        expert_idx[(size_t)t * k + s] = sel[s];
+        weights[(size_t)t * k + s] = w[s];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ stable grouping
+// A chunk is 256 consecutive flat assignments f, handled by one wave in four steps of 64.  Lanes holding the
+// same expert find each other with one ballot per bit of the expert index; the running per-expert count of
+// the chunk lives in a wave-private LDS array.  No order-dependent atomics anywhere: ranks are deterministic.
+constexpr int kChunk = 256;
+
+template <class Emit>
+__device__ __forceinline__ void chunk_ranks(const int32_t* __restrict__ expert_idx, int F, int chunk, int E, int nbits,
+                                            int* cnt, Emit&& emit) {
+  const int lane = threadIdx.x & 63;
+  for (int e = lane; e < E; e += 64) cnt[e] = 0;
+  __builtin_amdgcn_wave_barrier();
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int step = 0; step < kChunk / 64; ++step) {
+    const int f = chunk * kChunk + step * 64 + lane;
+    const bool valid = f < F;
+    const int e = valid ? expert_idx[f] : 0;
+    unsigned long long mask = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+      const bool bit = (e >> b) & 1;
+      const unsigned long long bal = __ballot(valid && bit);
+      mask &= bit ? bal : ~bal;
+    }
+    const int rank = __popcll(mask & below);
+    const int size = __popcll(mask);
+    const int base = valid ? cnt[e] : 0;
+    __builtin_amdgcn_wave_barrier();
+    if (valid && rank == 0) cnt[e] = base + size;
+    __builtin_amdgcn_wave_barrier();
+    if (valid) emit(f, e, base + rank);
+  }
+}
+
+__global__ void __launch_bounds__(256) chunk_hist_kernel(const int32_t* __restrict__ expert_idx, int F, int E, int nbits,
+                                                         int nchunks, int32_t* __restrict__ chunk_counts) {
+  __shared__ int cnt_all[4 * kMaxExperts];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int* cnt = cnt_all + wave * kMaxExperts;
+  const int chunk = blockIdx.x * 4 + wave;
+  if (chunk >= nchunks) return;
+  chunk_ranks(expert_idx, F, chunk, E, nbits, cnt, [](int, int, int) {});
+  __builtin_amdgcn_wave_barrier();
+  for (int e = lane; e < E; e += 64) chunk_counts[(size_t)chunk * E + e] = cnt[e];
+}
+
+// Single workgroup.  Turns chunk_counts into exclusive per-expert bases (in place), and writes
+// tokens_per_expert, padded_offsets (rows per expert = ceil(n_e/128)*128, Section 5.2), counts and expert_order.
+__global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
+                                                       int32_t* __restrict__ tokens_per_expert,
+                                                       int32_t* __restrict__ padded_offsets, int32_t* __restrict__ counts,
+                                                       int32_t* __restrict__ expert_order) {
+  __shared__ int n_s[kMaxExperts];
+  __shared__ int scan_s[kMaxExperts];
+  const int tid = threadIdx.x;
+  int n = 0;
+  if (tid < E) {
+    for (int c = 0; c < nchunks; ++c) {
+      const int v = chunk_counts[(size_t)c * E + tid];
+      chunk_counts[(size_t)c * E + tid] = n;
+      n += v;
+    }
+    tokens_per_expert[tid] = n;
+  }
+  const int padded = ((n + kBlock - 1) / kBlock) * kBlock;
+  n_s[tid] = n;
+  scan_s[tid] = tid < E ? padded : 0;
+  __syncthreads();
+  for (int off = 1; off < kMaxExperts; off <<= 1) {       // inclusive Hillis-Steele scan over experts
+    const int add = tid >= off ? scan_s[tid - off] : 0;
+    __syncthreads();
+    scan_s[tid] += add;
+    __syncthreads();
+  }
+  if (tid < E) padded_offsets[tid + 1] = scan_s[tid];
+  if (tid == 0) {
+    padded_offsets[0] = 0;
+    const int P = scan_s[E - 1];
+    counts[0] = P;
+    counts[1] = P / kBlock;
+    counts[2] = (P / kBlock) * hb;
+    counts[3] = 0;
+  }
+  if (tid < E) {                                           // position of expert `tid` in descending-load order
+    int pos = 0;
+    for (int o = 0; o < E; ++o) {
+      const int no = n_s[o];
+      pos += (no > n) || (no == n && o < tid);
+    }
+    expert_order[pos] = tid;
+  }
+}
+
+__global__ void __launch_bounds__(256) rank_kernel(const int32_t* __restrict__ expert_idx, int F, int E, int nbits,
+                                                   int nchunks, const int32_t* __restrict__ chunk_base,
+                                                   const int32_t* __restrict__ padded_offsets,
+                                                   int32_t* __restrict__ row_of, int32_t* __restrict__ token_of) {
+  __shared__ int cnt_all[4 * kMaxExperts];
+  const int wave = threadIdx.x >> 6;
+  int* cnt = cnt_all + wave * kMaxExperts;
+  const int chunk = blockIdx.x * 4 + wave;
+  if (chunk >= nchunks) return;
+  const int32_t* base = chunk_base + (size_t)chunk * E;
+  chunk_ranks(expert_idx, F, chunk, E, nbits, cnt, [&](int f, int e, int r) {
+    const int row = padded_offsets[e] + base[e] + r;
+    row_of[f] = row;
+    token_of[row] = f;
+  });
+}
+
+// ------------------------------------------------------------------------------------------------ topology
+// Expert owning block-row r: the last e with first_row[e] <= r (empty experts own nothing).
+__device__ __forceinline__ int owner_of_block_row(const int* first_row, int E, int r) {
+  int lo = 0, hi = E;                    // invariant: first_row[lo] <= r < first_row[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (first_row[mid] <= r) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// One thread per index.  Primary order numbers the nonzero blocks row by row (valid both as blocked CSR and
+// as blocked COO); the transposed order lists, column by column, the block-row of each block and the number
+// that block has in the primary order, so the values never have to be moved (Section 5.1.4).
+__global__ void __launch_bounds__(256) topology_kernel(const int32_t* __restrict__ padded_offsets,
+                                                       const int32_t* __restrict__ tokens_per_expert, int E, int hb,
+                                                       int32_t* __restrict__ row_offsets, int32_t* __restrict__ column_indices,
+                                                       int32_t* __restrict__ row_indices, int32_t* __restrict__ column_offsets_t,
+                                                       int32_t* __restrict__ row_indices_t, int32_t* __restrict__ block_offsets_t,
+                                                       int32_t* __restrict__ token_of) {
+  __shared__ int first_row[kMaxExperts + 1];
+  for (int e = threadIdx.x; e <= E; e += 256) first_row[e] = padded_offsets[e] / kBlock;
+  __syncthreads();
+  const int R = first_row[E];
+  const int nnz = R * hb;
+  const int P = R * kBlock;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+
+  if (idx < nnz) {
+    const int r = idx / hb;
+    const int e = owner_of_block_row(first_row, E, r);
+    column_indices[idx] = e * hb + idx % hb;
+    row_indices[idx] = r;
+    const int rows_e = first_row[e + 1] - first_row[e];
+    const int local = idx - hb * first_row[e];
+    const int j = local / rows_e, jj = local % rows_e;
+    row_indices_t[idx] = first_row[e] + jj;
+    block_offsets_t[idx] = (first_row[e] + jj) * hb + j;
+  }
+  if (idx <= R) row_offsets[idx] = idx * hb;
+  if (idx <= E * hb) {
+    const int e = idx / hb, j = idx % hb;
+    const int rows_e = e < E ? first_row[e + 1] - first_row[e] : 0;
+    column_offsets_t[idx] = hb * first_row[e] + j * rows_e;
+  }
+  if (idx < P) {
+    const int e = owner_of_block_row(first_row, E, idx / kBlock);
+    if (idx - first_row[e] * kBlock >= tokens_per_expert[e]) token_of[idx] = -1;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ launchers
+static int pow2_at_least(int v, int cap) {
+  int p = 1;
+  while (p < v && p < cap) p <<= 1;
+  return p;
+}
+
+void launch_router(const dmoe_config& c, const bf16_t* x, const bf16_t* wr, const float* bias,
+                   const dmoe_topology_t& t, hipStream_t s) {
+  const int T = c.num_tokens, d = c.d_model, E = c.num_experts;
+  const int epad = pow2_at_least(E < 4 ? 4 : E, 64);
+#define DMOE_ROUTER_CASE(EP)                                                                                   \
+  case EP: {                                                                                                   \
+    constexpr int TT = 4 * (64 / EP) * kRouterTPT;                                                             \
+    hipLaunchKernelGGL(router_logits_kernel<EP>, dim3((T + TT - 1) / TT), dim3(256), 0, s, x, wr, bias,        \
+                       t.logits, T, d, E);                                                                     \
+  } break;
+  switch (epad) {
+    DMOE_ROUTER_CASE(4)
+    DMOE_ROUTER_CASE(8)
+    DMOE_ROUTER_CASE(16)
+    DMOE_ROUTER_CASE(32)
+    DMOE_ROUTER_CASE(64)
+  }
+#undef DMOE_ROUTER_CASE
+  const int g = pow2_at_least(E, 64);
+#define DMOE_TOPK_CASE(G)                                                                                      \
+  case G:                                                                                                      \
+    hipLaunchKernelGGL(topk_kernel<G>, dim3((T + 256 / G - 1) / (256 / G)), dim3(256), 0, s, t.logits,         \
+                       t.expert_idx, t.weights, T, E, c.top_k, c.normalize_topk);                              \
+    break;
+  switch (g) {
+    DMOE_TOPK_CASE(1)
+    DMOE_TOPK_CASE(2)
+    DMOE_TOPK_CASE(4)
+    DMOE_TOPK_CASE(8)
+    DMOE_TOPK_CASE(16)
+    DMOE_TOPK_CASE(32)
+    DMOE_TOPK_CASE(64)
+  }
+#undef DMOE_TOPK_CASE
+}
+
+void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_counts, int p_max, hipStream_t s) {
+  (void)p_max;
+  const int F = c.num_tokens * c.top_k, E = c.num_experts;
+  const int nchunks = (F + kChunk - 1) / kChunk;
+  int nbits = 0;
+  while ((1 << nbits) < E) ++nbits;
+  const int hb = c.ffn_hidden / kBlock;
+  hipLaunchKernelGGL(chunk_hist_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
+                     chunk_counts);
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kMaxExperts), 0, s, chunk_counts, nchunks, E, hb, t.tokens_per_expert,
+                     t.padded_offsets, t.counts, t.expert_order);
+  hipLaunchKernelGGL(rank_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
+                     chunk_counts, t.padded_offsets, t.row_of, t.token_of);
+}
+
+void launch_make_topology(const dmoe_config& c, const dmoe_topology_t& t, int p_max, int nnz_max, hipStream_t s) {
+  const int hb = c.ffn_hidden / kBlock;
+  int n = nnz_max > p_max ? nnz_max : p_max;
+  if (c.num_experts * hb + 1 > n) n = c.num_experts * hb + 1;
+  if (p_max / kBlock + 1 > n) n = p_max / kBlock + 1;
+  hipLaunchKernelGGL(topology_kernel, dim3((n + 255) / 256), dim3(256), 0, s, t.padded_offsets, t.tokens_per_expert,
+                     c.num_experts, hb, t.row_offsets, t.column_indices, t.row_indices, t.column_offsets_t,
+                     t.row_indices_t, t.block_offsets_t, t.token_of);
+}
+
+}  // namespace dmoe

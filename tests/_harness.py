@@ -1,0 +1,117 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, run the oracle, compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2211_15841_amd as dm
+from dmoe_inputs import Config, make_inputs, bf16_bits_to_f32
+from oracle import dmoe_oracle as orc
+
+INDEX_KEYS = ["expert_idx", "tokens_per_expert", "padded_offsets", "row_of", "token_of", "row_offsets",
+              "column_indices", "row_indices", "column_offsets_t", "row_indices_t", "block_offsets_t", "counts"]
+REL_TOL = 1e-2          # max |G - O| / max |O| per tensor (bf16 storage, fp32 accumulation)
+
+
+def to_dev(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_to_np(t: torch.Tensor) -> np.ndarray:
+    return bf16_bits_to_f32(t.detach().cpu().view(torch.int16).numpy().view(np.uint16)).astype(np.float64)
+
+
+def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
+    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk)
+    if poison:      # unwritten regions must not look like zeros (empty experts, padding rows)
+        for t in (ws.topology_mem, ws.saved, ws.scratch):
+            t.fill_(0xFF)
+        for t in (ws.y, ws.dx, ws.dw1, ws.dw2):
+            t.view(torch.int16).fill_(0x7FC1)
+        ws.dw_router.fill_(float("nan"))
+    dev = {k: to_dev(inp[k]) for k in ("x", "w_router", "w1", "w2")}
+    bias = torch.from_numpy(inp["router_bias"]).cuda() if inp.get("router_bias") is not None else None
+    ws.topology(dev["x"], dev["w_router"], bias)
+    ws.forward(dev["x"], dev["w1"], dev["w2"])
+    out = {"topo": {k: v.numpy() for k, v in ws.topology_arrays().items()}}
+    out["y"] = bf16_to_np(ws.y)
+    if backward:
+        dy = to_dev(inp["dy"])
+        ws.backward(dev["x"], dev["w_router"], dev["w1"], dev["w2"], dy)
+        torch.cuda.synchronize()
+        out["dx"] = bf16_to_np(ws.dx)
+        out["dw1"] = bf16_to_np(ws.dw1)
+        out["dw2"] = bf16_to_np(ws.dw2)
+        out["dw_router"] = ws.dw_router.cpu().numpy().astype(np.float64)
+    out["ws"] = ws
+    return out
+
+
+def run_oracle_indices(cfg: Config, inp: dict):
+    logits, idx, w, p = orc.route(inp["x"], inp["w_router"], inp["router_bias"], cfg.top_k, cfg.normalize_topk)
+    n, off, row_of, token_of = orc.permutation(idx, cfg.num_experts)
+    topo = orc.topology(off, cfg.ffn_hidden)
+    ref = dict(topo, logits=logits, expert_idx=idx, weights=w, probs=p, tokens_per_expert=n, padded_offsets=off,
+               row_of=row_of, token_of=token_of)
+    return ref
+
+
+def check_indices(gpu_topo: dict, ref: dict):
+    for key in INDEX_KEYS:
+        g, o = np.asarray(gpu_topo[key]), np.asarray(ref[key])
+        assert g.shape == o.shape, (key, g.shape, o.shape)
+        assert np.array_equal(g, o), "%s differs at %d positions" % (key, int((g != o).sum()))
+    assert np.array_equal(gpu_topo["logits"].view(np.uint32), ref["logits"].view(np.uint32)), "router scores not bit-exact"
+    assert np.allclose(gpu_topo["weights"], ref["weights"], rtol=2e-5, atol=1e-7)
+    # expert_order: a permutation sorted by descending load, ties by ascending expert
+    n = ref["tokens_per_expert"]
+    order = gpu_topo["expert_order"]
+    expect = sorted(range(len(n)), key=lambda e: (-int(n[e]), e))
+    assert order.tolist() == expect
+
+
+def rel_err(g: np.ndarray, o: np.ndarray) -> float:
+    denom = np.abs(o).max()
+    return float(np.abs(g - o).max() / denom) if denom > 0 else float(np.abs(g).max())
+
+
+def check_values(name: str, g: np.ndarray, o: np.ndarray, tol: float = REL_TOL):
+    assert g.shape == o.shape, (name, g.shape, o.shape)
+    assert np.all(np.isfinite(g)), "%s has non-finite values" % name
+    e = rel_err(g, o)
+    assert e <= tol, "%s: max relative error %.3e > %.1e" % (name, e, tol)
+    # Guard against localised damage (a wrong tile, a missed row) that the tensor-wide figure could hide: the
+    # same max-normalised error, taken over every 128x128 tile of the tensor separately.  Honest bf16 noise is
+    # about 2.3e-3 of the local scale per element (four roundings of 2^-9/sqrt(3) rms), i.e. below 1e-2 of a
+    # tile's maximum even at 4-5 sigma; a misplaced or missing tile scores about 1.
+    gmax = float(np.abs(o).max())
+    for i0 in range(0, o.shape[0], 128):
+        for j0 in range(0, o.shape[1], 128):
+            ot, gt = o[i0:i0 + 128, j0:j0 + 128], g[i0:i0 + 128, j0:j0 + 128]
+            allowed = 3e-2 * float(np.abs(ot).max()) + 1e-4 * gmax
+            worst = float(np.abs(gt - ot).max())
+            assert worst <= allowed, "%s tile (%d,%d): error %.3e > %.3e" % (name, i0, j0, worst, allowed)
+    return e
+
+
+def full_parity(cfg: Config, inp: dict | None = None):
+    """Run both sides in full and compare everything; returns the per-tensor errors."""
+    inp = inp or make_inputs(cfg)
+    gpu = run_gpu(cfg, inp)
+    ref = run_oracle_indices(cfg, inp)
+    check_indices(gpu["topo"], ref)
+    h = cfg.ffn_hidden
+    y = orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], h)
+    g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], ref["expert_idx"], ref["weights"],
+                     ref["probs"], h, cfg.normalize_topk)
+    errs = {"y": check_values("y", gpu["y"], y)}
+    for name in ("dx", "dw1", "dw2"):
+        errs[name] = check_values(name, gpu[name], g[name])
+    if np.abs(g["dw_router"]).max() > 1e-9:
+        errs["dw_router"] = check_values("dw_router", gpu["dw_router"], g["dw_router"])
+    else:
+        assert np.abs(gpu["dw_router"]).max() < 1e-4
+    for e in np.flatnonzero(ref["tokens_per_expert"] == 0):      # empty experts: exact zeros, not garbage
+        assert not gpu["dw1"][:, e * h:(e + 1) * h].any()
+        assert not gpu["dw2"][e * h:(e + 1) * h, :].any()
+    return errs, gpu, ref

@@ -1,0 +1,72 @@
+"""Host-side checks of the C-ABI library (no GPU): it loads, exports every symbol the header declares, sizes
+buffers as documented, and turns invalid arguments into error codes before anything could be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2211_15841_amd as dm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(T=1024, d=256, h=1024, E=4, k=1, block=128, act=0, norm=0):
+    return dm.DMoEConfig(T, d, h, E, k, block, act, norm)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "dmoe.h")).read()
+    declared = re.findall(r"^DMOE_API\s+(?:const\s+)?\w+\s*\*?\s*(dmoe_\w+)\s*\(", header, flags=re.M)
+    assert set(declared) >= {"dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
+                             "dmoe_last_error"}
+    lib = dm.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_sizes_follow_the_documented_bounds():
+    s = dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64))
+    assert s["P_max"] == 128 * ((8192 + 127 * 64) // 128)
+    assert s["nnz_max"] == s["P_max"] // 128 * 16
+    assert s["saved_bytes"] >= 2 * s["P_max"] * 512 * 2 + 2 * s["nnz_max"] * 128 * 128 * 2
+    for key in ("topology_bytes", "saved_bytes", "scratch_bytes"):
+        assert s[key] % 256 == 0
+    # fewer assignments than experts: at most one block-row per assignment
+    s2 = dm.dmoe_sizes(_cfg(T=3, d=128, h=128, E=64))
+    assert s2["P_max"] == 3 * 128
+
+
+@pytest.mark.parametrize("kw,frag", [
+    (dict(block=64), "block"), (dict(d=200), "d_model"), (dict(h=100), "ffn_hidden"), (dict(E=0), "num_experts"),
+    (dict(E=257), "num_experts"), (dict(k=0), "top_k"), (dict(k=5, E=4), "top_k"), (dict(k=9, E=16), "top_k"),
+    (dict(T=0), "num_tokens"), (dict(act=1), "activation"), (dict(norm=2), "normalize_topk"),
+])
+def test_invalid_configurations_are_rejected(kw, frag):
+    with pytest.raises(dm.DMoEError) as ei:
+        dm.dmoe_sizes(_cfg(**kw))
+    assert "dmoe error -1" in str(ei.value) and frag in str(ei.value)
+
+
+def test_bind_and_calls_validate_pointers_without_launching():
+    cfg = _cfg()
+    s = dm.dmoe_sizes(cfg)
+    fake = 0x7f0000000000                      # never dereferenced on the host: validation only
+    topo = dm.dmoe_topology_bind(cfg, fake, s["topology_bytes"])
+    assert topo.expert_idx == fake and topo.counts > fake
+    with pytest.raises(dm.DMoEError, match="-2"):
+        dm.dmoe_topology_bind(cfg, fake, s["topology_bytes"] - 1)
+    with pytest.raises(dm.DMoEError, match="aligned"):
+        dm.dmoe_topology_bind(cfg, fake + 8, s["topology_bytes"])
+    lib = dm.load_library()
+    rc = lib.dmoe_topology(ctypes.byref(cfg), None, fake, None, ctypes.byref(topo), fake, s["scratch_bytes"], None)
+    assert rc == -1 and "x is NULL" in dm.dmoe_last_error()
+    rc = lib.dmoe_topology(ctypes.byref(cfg), fake, fake, None, ctypes.byref(topo), fake, 16, None)
+    assert rc == -2
+    empty = dm.DMoETopology()
+    rc = lib.dmoe_forward(ctypes.byref(cfg), fake, fake, fake, ctypes.byref(empty), fake, fake, s["saved_bytes"],
+                          fake, s["scratch_bytes"], None)
+    assert rc == -1 and "bind" in dm.dmoe_last_error()
+    rc = lib.dmoe_backward(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.byref(topo), fake, 8, fake, fake, fake,
+                           fake, fake, fake, s["scratch_bytes"], None)
+    assert rc == -2
