@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X dMoE layer: one step = dmoe_topology + dmoe_forward + dmoe_backward on one batch.
+
+Prints ONE JSON line.  `value` is useful TFLOP/s = 12*T*k*d*h / time (six block-sparse products of 2*T*k*d*h
+flops each; padding rows, the router and the permutation kernels are not counted as useful work) with every
+input already resident in HBM.  `roofline` describes the slowest block-sparse product of the step, timed with
+HIP events recorded around that kernel on the stream it runs on, inside the timed steps.  `cpu_baseline` is the
+CPU oracle (fp64 numpy) timed once on the same workload on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config xs] [--also small_zipf1.0,...] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+MATMUL_STAGES = ["sdd", "dsd", "sddt", "dstd", "dsdt", "ddts"]
+# Configurations whose block-sparse products are bound by HBM (weights are read once per ~128 rows: about
+# 128 flop/byte, below the 312 flop/byte ridge); the others are bound by the MFMA pipes.
+HBM_BOUND = {"tiny", "xs"}
+# HBM traffic per launch (bytes) of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled
+# by a copy kernel of known size; filled in from the summaries under profiles/ when they exist.
+MEASURED_TRAFFIC = {}
+
+
+class HipEvents:
+    """Minimal access to hipEvent_* of the HIP runtime that torch already loaded."""
+
+    def __init__(self):
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self.hip = ctypes.CDLL(path if os.path.exists(path) else "libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        assert rc == 0, "hipEventCreate failed: %d" % rc
+        return e
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, "hipEventElapsedTime failed: %d" % rc
+        return ms.value
+
+
+def algorithmic_bytes(stage: str, T, k, d, h, E, P, active) -> float:
+    """Bytes a kernel must move at least once (bf16 = 2 bytes): its dense operand rows, the weights of the
+    experts that own at least one token, the sparse blocks it reads or writes."""
+    pd, ph, w = P * d * 2.0, P * h * 2.0, active * d * h * 2.0
+    return {
+        "sdd": pd + w + 2 * ph,          # read Xp, W1; write H and gelu(H)
+        "dsd": ph + w + pd,              # read A, W2; write Yp
+        "sddt": pd + w + 2 * ph,         # read dYp, W2, H; write dH
+        "dstd": ph + pd + E * d * h * 2.0,   # read A, dYp; write all of dW2 (zeros for empty experts)
+        "dsdt": ph + w + pd,             # read dH, W1; write dXp
+        "ddts": pd + ph + E * d * h * 2.0,   # read Xp, dH; write all of dW1
+    }[stage]
+
+
+def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True):
+    import numpy as np
+    import torch
+    import paper_2211_15841_amd as dm
+    from dmoe_inputs import make_inputs
+
+    def log(*a):
+        if verbose:
+            print(*a, file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    inp = make_inputs(cfg)
+    log("[bench] %s: inputs drawn in %.1fs" % (cfg.name, time.time() - t0))
+    to_dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    x, wr, w1, w2, dy = (to_dev(inp[k]) for k in ("x", "w_router", "w1", "w2", "dy"))
+    bias = torch.from_numpy(inp["router_bias"]).cuda() if inp["router_bias"] is not None else None
+    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk)
+
+    def step():
+        ws.topology(x, wr, bias)
+        ws.forward(x, w1, w2)
+        ws.backward(x, wr, w1, w2, dy)
+
+    nst = len(dm.STAGE_NAMES)
+    EvArr = ctypes.c_void_p * (2 * nst)
+
+    # -- warm-up, with a per-stage timing pass to find the slowest block-sparse product --------------------
+    for _ in range(max(1, warmup // 2)):
+        step()
+    torch.cuda.synchronize()
+    stage_ms = {n: 0.0 for n in dm.STAGE_NAMES}
+    nprobe = max(3, warmup - warmup // 2)
+    for _ in range(nprobe):
+        evs = EvArr(*[hipev.create() for _ in range(2 * nst)])
+        dm.dmoe_set_stage_events(evs)
+        step()
+        dm.dmoe_set_stage_events(None)
+        torch.cuda.synchronize()
+        for i, n in enumerate(dm.STAGE_NAMES):
+            stage_ms[n] += hipev.elapsed_ms(evs[2 * i], evs[2 * i + 1]) / nprobe
+        for e in evs:
+            hipev.hip.hipEventDestroy(e)
+    dominant = max(MATMUL_STAGES, key=lambda n: stage_ms[n])
+    di = dm.STAGE_NAMES.index(dominant)
+
+    # -- timed region: exactly `steps` steps, events only around the dominant kernel -----------------------
+    ev_sets = []
+    for _ in range(steps):
+        arr = EvArr()
+        arr[2 * di], arr[2 * di + 1] = hipev.create(), hipev.create()
+        ev_sets.append(arr)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for arr in ev_sets:
+        dm.dmoe_set_stage_events(arr)
+        step()
+    dm.dmoe_set_stage_events(None)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    kernel_ms = sum(hipev.elapsed_ms(a[2 * di], a[2 * di + 1]) for a in ev_sets) / steps
+    for a in ev_sets:
+        hipev.hip.hipEventDestroy(a[2 * di]); hipev.hip.hipEventDestroy(a[2 * di + 1])
+
+    topo = ws.topology_arrays()
+    P, R, nnz, _ = (int(v) for v in topo["counts"])
+    n_e = topo["tokens_per_expert"].numpy()
+    active = int((n_e > 0).sum())
+    T, k, d, h, E = cfg.num_tokens, cfg.top_k, cfg.d_model, cfg.ffn_hidden, cfg.num_experts
+    ms = elapsed * 1e3 / steps
+    useful = cfg.useful_flops
+    res = {
+        "workload": cfg.name, "ms_per_step": ms, "useful_tflops": useful / (ms * 1e-3) / 1e12,
+        "pct_mfma_peak": 100.0 * useful / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "padded_tflops": 12.0 * P * d * h / (ms * 1e-3) / 1e12,
+        "P": P, "nnz_blocks": nnz, "active_experts": active, "max_tokens_per_expert": int(n_e.max()),
+        "stage_ms": {n: round(v, 5) for n, v in stage_ms.items()},
+        "matmul_ms": round(sum(stage_ms[n] for n in MATMUL_STAGES), 5),
+    }
+    if cfg.name in HBM_BOUND:
+        ab = algorithmic_bytes(dominant, T, k, d, h, E, P, active)
+        ach = ab / (kernel_ms * 1e-3) / 1e9
+        res["roofline"] = {"kernel": dominant, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant)),
+                           "kernel_ms": kernel_ms, "algorithmic_bytes": ab}
+    else:
+        fl = 2.0 * T * k * d * h
+        ach = fl / (kernel_ms * 1e-3) / 1e12
+        res["roofline"] = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                           "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant)), "kernel_ms": kernel_ms,
+                           "algorithmic_flops": fl}
+    log("[bench] %s: %.3f ms/step, %.1f useful TFLOP/s (%.1f%% of bf16 peak); stages %s" %
+        (cfg.name, ms, res["useful_tflops"], res["pct_mfma_peak"], res["stage_ms"]))
+
+    if with_cpu:
+        from threadpoolctl import threadpool_info
+        from oracle import dmoe_oracle as orc
+        t1 = time.perf_counter()
+        logits, idx, w, p = orc.route(inp["x"], inp["w_router"], inp["router_bias"], k, cfg.normalize_topk)
+        n, off, row_of, token_of = orc.permutation(idx, E)
+        orc.topology(off, h)
+        orc.forward(inp["x"], inp["w1"], inp["w2"], idx, w, h)
+        orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], idx, w, p, h, cfg.normalize_topk)
+        cpu_s = time.perf_counter() - t1
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        # backward() recomputes the forward to get its intermediates: 18*T*k*d*h flops of matmul in total
+        res["cpu_baseline"] = {"value": useful / cpu_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                               "sample": "the whole %s workload once (route + permute + topology + forward + backward, "
+                                         "fp64 numpy), %.2f s, host has %d cpus" % (cfg.name, cpu_s, os.cpu_count())}
+        log("[bench] %s: oracle %.2f s on %d threads" % (cfg.name, cpu_s, threads))
+    del ws, x, wr, w1, w2, dy
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="xs", help="workload name (see dmoe_inputs.CONFIGS) or 1-based index")
+    ap.add_argument("--also", default="small_zipf1.0,medium_zipf1.2_top2",
+                    help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from dmoe_inputs import CONFIGS, CONFIG_BY_NAME
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    def pick(name):
+        return CONFIGS[int(name) - 1] if name.isdigit() else CONFIG_BY_NAME[name]
+
+    hipev = HipEvents()
+    cfg = pick(args.config)
+    main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu)
+    others = []
+    for name in [n for n in args.also.split(",") if n and n != cfg.name]:
+        others.append(run_config(pick(name), max(5, args.steps // 5), max(4, args.warmup // 2), hipev, with_cpu=False))
+
+    line = {
+        "metric": "dMoE FFN fwd+bwd useful TFLOP/s (bf16) + % MFMA peak, 1 MI355X",
+        "value": main_res["useful_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "num_tokens": cfg.num_tokens, "d_model": cfg.d_model,
+                   "ffn_hidden": cfg.ffn_hidden, "num_experts": cfg.num_experts, "top_k": cfg.top_k,
+                   "block": 128, "routing": "zipf(%.1f)-biased router" % cfg.zipf_s if cfg.zipf_s else "random router"},
+        "pct_mfma_peak": main_res["pct_mfma_peak"],
+        "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "roofline_kernel": main_res["roofline"]["kernel"], "roofline_kernel_ms": main_res["roofline"]["kernel_ms"],
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "detail": {k: main_res[k] for k in ("padded_tflops", "P", "nnz_blocks", "active_experts",
+                                            "max_tokens_per_expert", "stage_ms", "matmul_ms")},
+        "other_workloads": others,
+        "paper_context": "MegaBlocks reports up to 40% end-to-end speedup over Tutel and up to 2.4x over Megatron-LM "
+                         "on 8x A100 SXM4 80GB (fp16, CUDA 11.5); no absolute kernel throughput is published",
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
