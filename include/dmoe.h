@@ -80,8 +80,12 @@ typedef struct {
   int32_t *row_indices_t;      /* [nnz_max] transposed order: block-row of each entry, ascending in a column     */
   int32_t *block_offsets_t;    /* [nnz_max] transposed order: number of that block in the primary order          */
   int32_t *counts;             /* [4]       P, R, nnz, 0                                                         */
-  int32_t *expert_order;       /* [E]       experts by descending n_e (ties -> lower expert); schedules the
-                                            weight-gradient products heaviest first                              */
+  /* Scheduling aids of this implementation (not part of the paper's encoding):                                  */
+  int32_t *expert_order;       /* [E]       experts by descending n_e (ties -> lower expert); the weight-gradient
+                                            products visit the heaviest experts first                            */
+  int32_t *group_offsets;      /* [E+1]     block-rows of an expert are taken two at a time ("row groups");
+                                            first group of each expert, group_offsets[E] = number of groups      */
+  int32_t *row_group;          /* [G_max]   2*(first block-row of the group) + (1 if the group has a second row) */
 } dmoe_topology_t;
 
 /* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,

@@ -25,7 +25,7 @@ class DMoEConfig(ctypes.Structure):
 
 _TOPO_FIELDS = ["expert_idx", "weights", "logits", "tokens_per_expert", "padded_offsets", "row_of", "token_of",
                 "row_offsets", "column_indices", "row_indices", "column_offsets_t", "row_indices_t",
-                "block_offsets_t", "counts", "expert_order"]
+                "block_offsets_t", "counts", "expert_order", "group_offsets", "row_group"]
 
 
 class DMoETopology(ctypes.Structure):
@@ -182,6 +182,7 @@ class Workspace:
             return self.topology_mem[off:off + 4 * n].view(dtype).cpu()
 
         i32, f32 = torch.int32, torch.float32
+        groups = int(view("group_offsets", E + 1, i32)[E])
         return {
             "expert_idx": view("expert_idx", F, i32).reshape(c.num_tokens, c.top_k),
             "weights": view("weights", F, f32).reshape(c.num_tokens, c.top_k),
@@ -198,4 +199,6 @@ class Workspace:
             "block_offsets_t": view("block_offsets_t", nnz, i32),
             "counts": torch.tensor([P, R, nnz, 0], dtype=i32),
             "expert_order": view("expert_order", E, i32),
+            "group_offsets": view("group_offsets", E + 1, i32),
+            "row_group": view("row_group", groups, i32),
         }

@@ -23,7 +23,7 @@ static bool aligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 25
 
 struct Dims {
   int T, d, h, E, k, hb, db, F;
-  int p_max, r_max, nnz_max, nchunks, npart;
+  int p_max, r_max, nnz_max, g_max, nchunks, npart;
 };
 
 static int check_config(const dmoe_config* c, Dims* out) {
@@ -48,6 +48,8 @@ static int check_config(const dmoe_config* c, Dims* out) {
   long long pm = ((F + 127 * nonempty) / kBlock) * kBlock;
   if (pm / kBlock * m.hb >= (1ll << 27)) return fail(DMOE_EINVAL, "too many nonzero blocks");
   m.p_max = (int)pm; m.r_max = m.p_max / kBlock; m.nnz_max = m.r_max * m.hb;
+  m.g_max = (int)((m.r_max + nonempty + 1) / 2);   // sum_e ceil(rows_e / 2)
+  if ((long long)m.E * m.h * kBlock >= (1ll << 32)) return fail(DMOE_EINVAL, "num_experts*ffn_hidden too large");
   m.nchunks = (m.F + 255) / 256;
   m.npart = router_bwd_num_partials(*c);
   if (out) *out = m;
@@ -55,11 +57,11 @@ static int check_config(const dmoe_config* c, Dims* out) {
 }
 
 struct TopoLayout {
-  size_t off[15];
+  size_t off[17];
   size_t total;
 };
 static TopoLayout topo_layout(const Dims& m) {
-  const size_t n[15] = {
+  const size_t n[17] = {
       (size_t)m.F * 4,             // expert_idx
       (size_t)m.F * 4,             // weights
       (size_t)m.T * m.E * 4,       // logits
@@ -75,10 +77,12 @@ static TopoLayout topo_layout(const Dims& m) {
       (size_t)m.nnz_max * 4,       // block_offsets_t
       16,                          // counts
       (size_t)m.E * 4,             // expert_order
+      (size_t)(m.E + 1) * 4,       // group_offsets
+      (size_t)(m.g_max + 1) * 4,   // row_group
   };
   TopoLayout l;
   size_t at = 0;
-  for (int i = 0; i < 15; ++i) { l.off[i] = at; at += align_up(n[i]); }
+  for (int i = 0; i < 17; ++i) { l.off[i] = at; at += align_up(n[i]); }
   l.total = at;
   return l;
 }
@@ -113,10 +117,11 @@ static int check_ptr(const void* p, const char* name) {
 }
 static int check_topo(const dmoe_topology_t* t) {
   if (!t) return fail(DMOE_EINVAL, "topology is NULL");
-  const void* ps[15] = {t->expert_idx, t->weights, t->logits, t->tokens_per_expert, t->padded_offsets, t->row_of,
+  const void* ps[17] = {t->expert_idx, t->weights, t->logits, t->tokens_per_expert, t->padded_offsets, t->row_of,
                         t->token_of, t->row_offsets, t->column_indices, t->row_indices, t->column_offsets_t,
-                        t->row_indices_t, t->block_offsets_t, t->counts, t->expert_order};
-  for (int i = 0; i < 15; ++i)
+                        t->row_indices_t, t->block_offsets_t, t->counts, t->expert_order, t->group_offsets,
+                        t->row_group};
+  for (int i = 0; i < 17; ++i)
     if (!ps[i]) return fail(DMOE_EINVAL, "topology array %d is NULL (call dmoe_topology_bind first)", i);
   return DMOE_OK;
 }
@@ -167,6 +172,8 @@ int dmoe_topology_bind(const dmoe_config* cfg, void* topology_mem, size_t bytes,
   out->block_offsets_t = reinterpret_cast<int32_t*>(b + l.off[12]);
   out->counts = reinterpret_cast<int32_t*>(b + l.off[13]);
   out->expert_order = reinterpret_cast<int32_t*>(b + l.off[14]);
+  out->group_offsets = reinterpret_cast<int32_t*>(b + l.off[15]);
+  out->row_group = reinterpret_cast<int32_t*>(b + l.off[16]);
   return DMOE_OK;
 }
 
@@ -222,7 +229,7 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
   ev.end(DMOE_STAGE_GATHER);
 
   BsArgs a{};
-  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.r_max = m.r_max; a.nnz_max = m.nnz_max;
+  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max;
   ev.begin(DMOE_STAGE_SDD);
   a.dense_a = xp; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = nullptr; a.out0 = hval; a.out1 = aval;
   launch_bsmm(OP_SDD, a, s);
@@ -281,7 +288,7 @@ int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, c
   ev.end(DMOE_STAGE_BWD_GATHER);
 
   BsArgs a{};
-  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.r_max = m.r_max; a.nnz_max = m.nnz_max;
+  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max;
 
   ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * gelu'(H)
   a.dense_a = dyp; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = hval; a.out0 = dh; a.out1 = nullptr;

@@ -8,24 +8,32 @@
 //   DD^TS  dW1 = Xp^T dH        sparse rhs iterated through the transpose indices         (layer-1 weight gradient)
 //
 // Block size 128x128 (Section 5.1.2); values of block b (primary, row-wise order) are a contiguous row-major
-// 128x128 bf16 tile at offset b*16384.  SDD-type kernels find their block through row_indices/column_indices
-// (the COO half of the hybrid encoding, Section 5.1.3); DSD-type kernels walk row_offsets/column_indices;
-// the weight-gradient kernels walk column_offsets_t/row_indices_t/block_offsets_t (Section 5.1.4).
+// 128x128 bf16 tile at offset b*16384.  SDD-type kernels find their blocks through row_offsets/column_indices,
+// DSD-type kernels walk row_offsets/column_indices along K, the weight-gradient kernels walk
+// column_offsets_t/row_indices_t/block_offsets_t (Section 5.1.4) along K.
 //
-// One workgroup = 4 waves = one 128x128 output tile, K advanced 64 at a time through double-buffered LDS.
-// Each wave owns a 64x64 quadrant as 2x2 v_mfma_f32_32x32x16_bf16 tiles.  An operand whose K index is
-// contiguous in memory is staged as [row][64 k] and read with ds_read_b128; an operand whose K index is the
-// strided one is staged as it lies in memory, [k][128], and read with the transposing ds_read_b64_tr_b16, so
-// no operand is ever transposed in HBM or in registers.  Both stagings are XOR-swizzled instead of padded.
+// Tiling.  A 128x128 tile moves one operand byte per 64 flops, which on this chip saturates the L2->CU path
+// long before the MFMA pipes.  One workgroup (8 waves) therefore owns a 256x256 MACRO tile = 2x2 sparse
+// blocks: two "A panels" of 128 rows and two "B panels" of 128 columns, each panel an independent
+// 128x64 (K-contiguous) or 64x128 (K-strided) slab with its own base pointer, so that a macro tile can be
+// two block-rows of one expert times two block-columns, whichever operand is the sparse one.  A missing
+// panel (odd number of block-rows in an expert, odd h/128 or d/128) is simply skipped by the waves that own it.
+// K advances 64 at a time through two LDS stages filled by direct global->LDS loads (global_load_lds_dwordx4),
+// so operands never pass through registers on their way in.  Each wave computes 128x64 of the macro tile as
+// 4x2 v_mfma_f32_32x32x16_bf16 tiles.  K-contiguous slabs are read with ds_read_b128, K-strided slabs as they
+// lie in memory with the transposing ds_read_b64_tr_b16; both are XOR-swizzled instead of padded.
 #include "common.h"
+#include "mma_tile.h"
+#include <cstdlib>
 
 namespace dmoe {
 
-constexpr int kBK = 64;                       // K per pipeline stage
-constexpr int kTileBytes = 16384;             // 128 x 64 bf16 either way round
+// K per pipeline stage (BK) and number of LDS stages (NS) are template parameters of the kernel:
+// a slab is 128 x BK bf16 = 256*BK bytes either way round, a stage is four slabs (A0 A1 B0 B1).
 constexpr int kBlockElems = kBlock * kBlock;  // 16384 values per sparse block
+constexpr int kBsThreads = 512;
+constexpr int kPatch = 32;                    // macro tiles that should run together on one XCD (one per CU)
 
-enum Layout { KC = 0, NC = 1 };               // KC: [row][k] k-contiguous;  NC: [k][row] row-contiguous
 
 struct BsParams {
   const bf16_t* dense_a;
@@ -35,13 +43,14 @@ struct BsParams {
   bf16_t* out1;
   const int32_t* row_offsets;
   const int32_t* column_indices;
-  const int32_t* row_indices;
   const int32_t* column_offsets_t;
   const int32_t* row_indices_t;
   const int32_t* block_offsets_t;
-  const int32_t* counts;
+  const int32_t* group_offsets;
+  const int32_t* row_group;
   const int32_t* expert_order;
   int d, h, E, hb, db;
+  int dbg;
 };
 
 template <int OP> struct OpLayouts;
@@ -52,214 +61,249 @@ template <> struct OpLayouts<OP_DSTD> { static constexpr int A = NC, B = NC; };
 template <> struct OpLayouts<OP_DSDT> { static constexpr int A = KC, B = KC; };
 template <> struct OpLayouts<OP_DDTS> { static constexpr int A = NC, B = NC; };
 
-// ---- LDS addressing -------------------------------------------------------------------------------------------
-// KC tile: 128 rows x 128 bytes.  16-byte chunk c of row r sits at chunk c ^ ((r >> 1) & 7): the 16 lanes that a
-// ds_read_b128 serves per clock (16 consecutive rows, same logical chunk) then cover all 64 banks once.
-__device__ __forceinline__ int kc_offset(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
-// NC tile: 64 k-rows x 256 bytes.  32-byte unit u of k-row k sits at unit u ^ (2 * (k & 3)): the 32 lanes that a
-// ds_read_b64_tr_b16 serves per clock (4 k-rows x two adjacent units) then cover all 64 banks once.
-__device__ __forceinline__ int nc_offset(int krow, int chunk16) {
-  return krow * 256 + ((((chunk16 >> 1) ^ ((krow & 3) << 1)) << 5) | ((chunk16 & 1) << 4));
+// Workgroups are handed to the 8 XCDs round-robin (workgroup w runs on XCD w % 8).  Work items are cut into
+// patches of 32 consecutive items that share operands; patch p goes to XCD p % 8, so the 32 items of a patch run
+// side by side on the 32 CUs behind one L2, and heavy patches spread evenly over the XCDs.
+__device__ __forceinline__ int patch_item(int wg) {
+  const int xcd = wg & 7, slot = wg >> 3;
+  return ((slot / kPatch) * 8 + xcd) * kPatch + slot % kPatch;
 }
 
-template <int L>
-__device__ __forceinline__ void global_to_regs(uint4 (&regs)[4], const bf16_t* __restrict__ base, size_t ld, int tid) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = tid + 256 * i;
-    const int row = L == KC ? (q >> 3) : (q >> 4);
-    const int c = L == KC ? (q & 7) : (q & 15);
-    regs[i] = *reinterpret_cast<const uint4*>(base + (size_t)row * ld + c * 8);
-  }
-}
-template <int L>
-__device__ __forceinline__ void regs_to_lds(const uint4 (&regs)[4], char* lds, int tid) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int q = tid + 256 * i;
-    const int off = L == KC ? kc_offset(q >> 3, q & 7) : nc_offset(q >> 4, q & 15);
-    *reinterpret_cast<uint4*>(lds + off) = regs[i];
-  }
-}
-
-typedef __attribute__((address_space(3))) s16x4_v* lds_s16x4_ptr;
-
-// MFMA operand for the 32 rows starting at `row0` of the tile and K step ks (16 k): lane l gets row row0 + l%32
-// and the 8 consecutive k = 16 ks + 8 (l / 32) + 0..7, whichever way round the tile is staged.
-template <int L>
-__device__ __forceinline__ bf16x8_v load_frag(const char* lds, int row0, int ks, int lane) {
-  if constexpr (L == KC) {
-    const int row = row0 + (lane & 31);
-    return *reinterpret_cast<const bf16x8_v*>(lds + kc_offset(row, 2 * ks + (lane >> 5)));
-  } else {
-    // ds_read_b64_tr_b16 works on groups of 16 lanes: lane i of a group receives element i of each of the four
-    // 16-element rows whose addresses are supplied by lanes 4j..4j+3 (j = 0..3) of the group.
-    const int l16 = lane & 15;
-    const int kq = l16 >> 2;                                   // k-row (mod 4) this lane supplies the address of
-    const int unit = (row0 >> 4) + ((lane >> 4) & 1);
-    const int k0 = 16 * ks + 8 * (lane >> 5) + kq;
-    const int off0 = k0 * 256 + ((unit ^ (kq << 1)) << 5) + ((l16 & 3) << 3);
-    const int off1 = off0 + 4 * 256;                           // k0 + 4 has the same k & 3
-    const s16x4_v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + off0));
-    const s16x4_v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + off1));
-    union { struct { s16x4_v a, b; } s; bf16x8_v v; } u;
-    u.s.a = lo;
-    u.s.b = hi;
-    return u.v;
-  }
-}
-
-// Workgroup index -> tile index.  Workgroups are handed to the 8 XCDs round-robin; this gives each XCD a
-// contiguous run of tiles so that tiles sharing operands meet in the same L2.
-__device__ __forceinline__ int xcd_remap(int wg, int total) {
-  const int per = total >> 3;
-  if (wg >= (per << 3)) return wg;                 // ragged tail (and workgroups beyond `total`) keep their index
-  return (wg & 7) * per + (wg >> 3);
-}
-
-template <int OP>
-__global__ void __launch_bounds__(256, 2) bsmm_kernel(const BsParams p) {
+template <int OP, int BK, int NS>
+__global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];
+  constexpr int kBK = BK;
+  constexpr int kSub = kBlock / BK;                 // K tiles per 128-wide sparse block
+  constexpr int kSubShift = BK == 64 ? 1 : 2;
+  constexpr int kPanelBytes = 256 * BK;
+  constexpr int kStageBytes = 4 * kPanelBytes;
+  constexpr int kCpw = kPanelBytes / 8192;          // 1 KB DMA chunks per wave per slab
+  constexpr int kDmaPerTile = 4 * kCpw;             // DMA instructions per wave per K tile
+  extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A0 A1 B0 B1][slab]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int pm = wave >> 2, pn = (wave >> 1) & 1, hn = wave & 1;
   const int d = p.d, hb = p.hb, db = p.db;
   const size_t ldw = (size_t)p.E * p.h;            // leading dimension of W1 / dW1
+  const int ncp = (hb + 1) >> 1, njp = (db + 1) >> 1;
 
-  // ---- which tile ----------------------------------------------------------------------------------------
-  int nk = 0, first = 0, r = 0, c = 0, j = 0;
-  if constexpr (OP == OP_SDD || OP == OP_SDDT) {
-    const int nnz = p.counts[2];
-    if ((int)blockIdx.x >= nnz) return;
-    const int b = xcd_remap(blockIdx.x, nnz);
-    first = b;
-    r = p.row_indices[b];
-    c = p.column_indices[b];
-    nk = d / kBK;
-  } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-    const int tiles = p.counts[1] * db;
-    if ((int)blockIdx.x >= tiles) return;
-    const int wg = xcd_remap(blockIdx.x, tiles);
-    r = wg / db;
-    j = wg % db;
-    first = p.row_offsets[r];
-    nk = 2 * (p.row_offsets[r + 1] - first);
+  // ---- which macro tile --------------------------------------------------------------------------------------
+  // Items are numbered so that 4 consecutive "major" indices (row groups / column pairs) times all "minor"
+  // indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
+  const int item = patch_item(blockIdx.x);
+  int major, minor;
+  {
+    const int nminor = (OP == OP_SDD || OP == OP_SDDT) ? ncp : njp;
+    const int run = item / (4 * nminor), rem = item % (4 * nminor);
+    major = run * 4 + (rem & 3);
+    minor = rem >> 2;
+  }
+  bool a_ok[2] = {true, false}, b_ok[2] = {true, false};
+  int nk = 0;
+  int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jp = 0;
+  if constexpr (OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT) {
+    const int G = p.group_offsets[p.E];
+    if (major >= G) return;
+    const int rg = p.row_group[major];             // first block-row * 2 + (group has a second row)
+    r0 = rg >> 1;
+    a_ok[1] = rg & 1;
+    r1 = a_ok[1] ? r0 + 1 : r0;
+    first0 = p.row_offsets[r0];
+    first1 = p.row_offsets[r1];
+    const int nblk = p.row_offsets[r0 + 1] - first0;
+    if constexpr (OP == OP_SDD || OP == OP_SDDT) {
+      if (2 * minor >= nblk) return;
+      b_ok[1] = 2 * minor + 1 < nblk;
+      first0 += 2 * minor;                         // block (r0, c0); (r0, c1) is the next one
+      first1 += 2 * minor;
+      c0 = p.column_indices[first0];
+      c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
+      nk = d / kBK;
+      if (p.dbg & 4) { r0 = r1 = 0; c0 = c1 = p.column_indices[0]; }   // experiment: every tile reads the same slabs
+      if (p.dbg & 8) { c0 = c1 = p.column_indices[0]; }
+      if (p.dbg & 16) { r0 = r1 = 0; }
+    } else {
+      jp = minor;
+      b_ok[1] = 2 * jp + 1 < db;
+      nk = kSub * nblk;
+    }
   } else {
-    const int wg = blockIdx.x;
-    const int cs = wg / db;
-    j = wg % db;
-    const int e = p.expert_order[cs / hb];         // heaviest experts first
-    c = e * hb + cs % hb;
-    first = p.column_offsets_t[c];
-    nk = 2 * (p.column_offsets_t[c + 1] - first);
+    if (major >= p.E * ncp) return;
+    const int e = p.expert_order[major / ncp];     // heaviest experts first
+    const int cp = major % ncp;
+    jp = minor;
+    c0 = e * hb + 2 * cp;
+    const bool second_col = 2 * cp + 1 < hb;
+    c1 = second_col ? c0 + 1 : c0;
+    first0 = p.column_offsets_t[c0];
+    first1 = p.column_offsets_t[c1];
+    nk = kSub * (p.column_offsets_t[c0 + 1] - first0);
+    if constexpr (OP == OP_DSTD) { a_ok[1] = second_col;  b_ok[1] = 2 * jp + 1 < db; }
+    else                         { a_ok[1] = 2 * jp + 1 < db;  b_ok[1] = second_col; }
   }
 
-  const bf16_t* a_ptr;
-  const bf16_t* b_ptr;
-  size_t lda, ldb;
-  auto tile_ptrs = [&](int kt) {
+  // ---- per-K-tile slab base pointers (wave-uniform) ----------------------------------------------------------
+  const bf16_t *a0, *a1, *b0, *b1;
+  uint32_t lda, ldb;
+  if constexpr (OP == OP_SDD)       { lda = d;      ldb = (uint32_t)ldw; }
+  else if constexpr (OP == OP_SDDT) { lda = d;      ldb = d; }
+  else if constexpr (OP == OP_DSD)  { lda = kBlock; ldb = d; }
+  else if constexpr (OP == OP_DSDT) { lda = kBlock; ldb = (uint32_t)ldw; }
+  else if constexpr (OP == OP_DSTD) { lda = kBlock; ldb = d; }
+  else                              { lda = d;      ldb = kBlock; }
+
+  auto slab_ptrs = [&](int kt) {
     if constexpr (OP == OP_SDD) {
-      a_ptr = p.dense_a + (size_t)r * kBlock * d + kt * kBK;  lda = d;
-      b_ptr = p.dense_b + (size_t)kt * kBK * ldw + (size_t)c * kBlock;  ldb = ldw;
+      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * kBK;
+      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * kBK;
+      b0 = p.dense_b + (size_t)kt * kBK * ldw + (size_t)c0 * kBlock;
+      b1 = p.dense_b + (size_t)kt * kBK * ldw + (size_t)c1 * kBlock;
     } else if constexpr (OP == OP_SDDT) {
-      a_ptr = p.dense_a + (size_t)r * kBlock * d + kt * kBK;  lda = d;
-      b_ptr = p.dense_b + (size_t)c * kBlock * d + kt * kBK;  ldb = d;
+      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * kBK;
+      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * kBK;
+      b0 = p.dense_b + (size_t)c0 * kBlock * d + kt * kBK;
+      b1 = p.dense_b + (size_t)c1 * kBlock * d + kt * kBK;
     } else if constexpr (OP == OP_DSD) {
-      const int blk = first + (kt >> 1), half = kt & 1;
-      const int col = p.column_indices[blk];
-      a_ptr = p.sparse_in + (size_t)blk * kBlockElems + half * kBK;  lda = kBlock;
-      b_ptr = p.dense_b + ((size_t)col * kBlock + half * kBK) * d + j * kBlock;  ldb = d;
+      const int kb = kt >> kSubShift, half = kt & (kSub - 1);
+      const int col = p.column_indices[first0 + kb];
+      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * kBK;
+      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * kBK;
+      b0 = p.dense_b + ((size_t)col * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else if constexpr (OP == OP_DSDT) {
-      const int blk = first + (kt >> 1), half = kt & 1;
-      const int col = p.column_indices[blk];
-      a_ptr = p.sparse_in + (size_t)blk * kBlockElems + half * kBK;  lda = kBlock;
-      b_ptr = p.dense_b + (size_t)j * kBlock * ldw + (size_t)col * kBlock + half * kBK;  ldb = ldw;
+      const int kb = kt >> kSubShift, half = kt & (kSub - 1);
+      const int col = p.column_indices[first0 + kb];
+      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * kBK;
+      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * kBK;
+      b0 = p.dense_b + (size_t)(2 * jp) * kBlock * ldw + (size_t)col * kBlock + half * kBK;
+      b1 = b0 + (b_ok[1] ? (size_t)kBlock * ldw : 0);
     } else if constexpr (OP == OP_DSTD) {
-      const int i = first + (kt >> 1), half = kt & 1;
-      const int blk = p.block_offsets_t[i], row = p.row_indices_t[i];
-      a_ptr = p.sparse_in + (size_t)blk * kBlockElems + half * kBK * kBlock;  lda = kBlock;
-      b_ptr = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + j * kBlock;  ldb = d;
+      const int i = kt >> kSubShift, half = kt & (kSub - 1);
+      const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
+      const int row = p.row_indices_t[first0 + i];
+      a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * kBK * kBlock;
+      a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * kBK * kBlock;
+      b0 = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else {  // OP_DDTS
-      const int i = first + (kt >> 1), half = kt & 1;
-      const int blk = p.block_offsets_t[i], row = p.row_indices_t[i];
-      a_ptr = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + j * kBlock;  lda = d;
-      b_ptr = p.sparse_in + (size_t)blk * kBlockElems + half * kBK * kBlock;  ldb = kBlock;
+      const int i = kt >> kSubShift, half = kt & (kSub - 1);
+      const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
+      const int row = p.row_indices_t[first0 + i];
+      a0 = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      a1 = a0 + (a_ok[1] ? kBlock : 0);
+      b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * kBK * kBlock;
+      b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * kBK * kBlock;
     }
   };
 
-  f32x16_v acc[2][2];
+  // Each wave moves 1 KB chunk `wave` (and `wave + 8` when a slab has 16 of them) of every slab.  All four slabs are
+  // always loaded, a missing panel re-reads its sibling: the number of loads per K tile must be a constant for the
+  // counted waits below.
+  uint32_t oa[kCpw], ob[kCpw];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < kCpw; ++i) {
+    oa[i] = dma_lane_offset<LA, BK>(wave + 8 * i, lane, lda);
+    ob[i] = dma_lane_offset<LB, BK>(wave + 8 * i, lane, ldb);
+  }
+  // The loads are written as inline assembly on purpose: the compiler's own wait-count insertion treats a
+  // direct-to-LDS load as aliasing every later LDS read and would wait for it before the first ds_read of the
+  // stage being computed, which serialises load latency and MFMA work.  Here the waits are explicit.
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
+  auto dma16 = [](const bf16_t* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory");
+  };
+  // part 0 = the two A slabs, part 1 = the two B slabs (issued at different points of the MFMA loop, see below)
+  auto issue_loads = [&](int stage, int part) {
+    const uint32_t s = __builtin_amdgcn_readfirstlane(lds_base + stage * kStageBytes + wave * 1024);
+#pragma unroll
+    for (int i = 0; i < kCpw; ++i) {
+      if (part == 0) {
+        dma16(a0 + oa[i], s + 8192 * i);
+        dma16(a1 + oa[i], s + kPanelBytes + 8192 * i);
+      } else {
+        dma16(b0 + ob[i], s + 2 * kPanelBytes + 8192 * i);
+        dma16(b1 + ob[i], s + 3 * kPanelBytes + 8192 * i);
+      }
+    }
+  };
+
+  f32x16_v acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][jj][q] = 0.0f;
 
-  uint4 ra[4], rb[4];
-  if (nk > 0) {
-    tile_ptrs(0);
-    global_to_regs<LA>(ra, a_ptr, lda, tid);
-    global_to_regs<LB>(rb, b_ptr, ldb, tid);
-    regs_to_lds<LA>(ra, lds[0][0], tid);
-    regs_to_lds<LB>(rb, lds[0][1], tid);
-  }
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      tile_ptrs(kt + 1);
-      global_to_regs<LA>(ra, a_ptr, lda, tid);
-      global_to_regs<LB>(rb, b_ptr, ldb, tid);
+  const bool mine = a_ok[pm] && b_ok[pn];          // this wave's quadrant exists
+  // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
+  // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
+  // t has landed; near the end of K, when fewer tiles are in flight, the wait is for everything.
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) {
+    if (t < nk) {
+      slab_ptrs(t);
+      issue_loads(t, 0);
+      issue_loads(t, 1);
     }
-    const char* sa = lds[cur][0];
-    const char* sb = lds[cur][1];
+  }
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + NS - 2 < nk) asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * kDmaPerTile) : "memory");
+    else                  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                               // tile kt visible to all; everyone is done with tile kt-1
+    const bool more = kt + NS - 1 < nk && !(p.dbg & 2);
+    const int next_stage = (kt + NS - 1) % NS;
+    if (more) slab_ptrs(kt + NS - 1);
+    const char* sa = lds + (kt % NS) * kStageBytes + pm * kPanelBytes;
+    const char* sb = lds + (kt % NS) * kStageBytes + (2 + pn) * kPanelBytes;
+    // The loads of the next tile are spread over the first two K steps instead of being issued in one burst: a
+    // wave cannot start its MFMAs before its own loads have been issued, and 64 back-to-back 1 KB loads keep the
+    // CU's address unit busy for about a thousand cycles.
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8_v af[2], bf[2];
-      af[0] = load_frag<LA>(sa, wm * 64, ks, lane);
-      af[1] = load_frag<LA>(sa, wm * 64 + 32, ks, lane);
-      bf[0] = load_frag<LB>(sb, wn * 64, ks, lane);
-      bf[1] = load_frag<LB>(sb, wn * 64 + 32, ks, lane);
-      // Operands swapped on purpose: the MFMA "row" index runs over n and the "column" index over m, so each lane
-      // ends up with four consecutive n of one output row and can store them as one 8-byte word.
+      if (more && ks < 2) issue_loads(next_stage, ks);
+      if (mine && !(p.dbg & 1)) {
+        bf16x8_v af[4], bf[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 4; ++i) af[i] = load_frag<LA, BK>(sa, 32 * i, ks, lane);
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[jj], af[i], acc[i][jj], 0, 0, 0);
+        for (int jj = 0; jj < 2; ++jj) bf[jj] = load_frag<LB, BK>(sb, hn * 64 + 32 * jj, ks, lane);
+        // Operands swapped on purpose: the MFMA "row" index runs over n and the "column" index over m, so each
+        // lane ends up with four consecutive n of one output row and can store them as one 8-byte word.
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj)
+            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[jj], af[i], acc[i][jj], 0, 0, 0);
+      }
     }
-    if (more) {
-      regs_to_lds<LA>(ra, lds[cur ^ 1][0], tid);
-      regs_to_lds<LB>(rb, lds[cur ^ 1][1], tid);
-    }
-    __syncthreads();
   }
+  if (!mine) return;
 
   // ---- epilogue: lane l, accumulator register 4q+u of tile (i, jj) is
-  //      C[wm*64 + 32 i + l%32][wn*64 + 32 jj + 8 q + 4 (l/32) + u]
+  //      C[32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn)
   bf16_t* out;
   size_t ldo;
+  size_t blk = 0;
   if constexpr (OP == OP_SDD || OP == OP_SDDT) {
-    out = p.out0 + (size_t)first * kBlockElems;  ldo = kBlock;
+    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems;
+    out = p.out0 + blk;  ldo = kBlock;
   } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-    out = p.out0 + (size_t)r * kBlock * d + j * kBlock;  ldo = d;
+    out = p.out0 + (size_t)(pm ? r1 : r0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock;  ldo = d;
   } else if constexpr (OP == OP_DSTD) {
-    out = p.out0 + (size_t)c * kBlock * d + j * kBlock;  ldo = d;
+    out = p.out0 + (size_t)(pm ? c1 : c0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock;  ldo = d;
   } else {
-    out = p.out0 + (size_t)j * kBlock * ldw + (size_t)c * kBlock;  ldo = ldw;
+    out = p.out0 + (size_t)(2 * jp + pm) * kBlock * ldw + (size_t)(pn ? c1 : c0) * kBlock;  ldo = ldw;
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = wm * 64 + 32 * i + (lane & 31);
+  for (int i = 0; i < 4; ++i) {
+    const int m = 32 * i + (lane & 31);
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = wn * 64 + 32 * jj + 8 * q + 4 * (lane >> 5);
+        const int n = hn * 64 + 32 * jj + 8 * q + 4 * (lane >> 5);
         const float v0 = acc[i][jj][4 * q + 0], v1 = acc[i][jj][4 * q + 1];
         const float v2 = acc[i][jj][4 * q + 2], v3 = acc[i][jj][4 * q + 3];
         const size_t o = (size_t)m * ldo + n;
@@ -268,9 +312,9 @@ __global__ void __launch_bounds__(256, 2) bsmm_kernel(const BsParams p) {
           hv.x = pack_bf16(v0, v1);  hv.y = pack_bf16(v2, v3);
           av.x = pack_bf16(gelu_fwd(v0), gelu_fwd(v1));  av.y = pack_bf16(gelu_fwd(v2), gelu_fwd(v3));
           *reinterpret_cast<uint2*>(out + o) = hv;
-          *reinterpret_cast<uint2*>(p.out1 + (size_t)first * kBlockElems + o) = av;
+          *reinterpret_cast<uint2*>(p.out1 + blk + o) = av;
         } else if constexpr (OP == OP_SDDT) {
-          const uint2 hv = *reinterpret_cast<const uint2*>(p.sparse_in + (size_t)first * kBlockElems + o);
+          const uint2 hv = *reinterpret_cast<const uint2*>(p.sparse_in + blk + o);
           uint2 gv;
           gv.x = pack_bf16(v0 * gelu_bwd(bf16_lo(hv.x)), v1 * gelu_bwd(bf16_hi(hv.x)));
           gv.y = pack_bf16(v2 * gelu_bwd(bf16_lo(hv.y)), v3 * gelu_bwd(bf16_hi(hv.y)));
@@ -285,22 +329,50 @@ __global__ void __launch_bounds__(256, 2) bsmm_kernel(const BsParams p) {
   }
 }
 
+template <int OP, int BK, int NS>
+static void launch_variant(const BsParams& p, int items, hipStream_t s) {
+  static bool configured = false;
+  constexpr int kLds = NS * 4 * 256 * BK;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, BK, NS>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    configured = true;
+  }
+  const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
+  hipLaunchKernelGGL((bsmm_kernel<OP, BK, NS>), dim3(grid), dim3(kBsThreads), kLds, s, p);
+}
+template <int OP>
+static void launch_one(const BsParams& p, int items, hipStream_t s) {
+  static int variant = -1;
+  if (variant < 0) { const char* e = getenv("DMOE_VARIANT"); variant = e ? atoi(e) : 0; }
+  switch (variant) {
+    case 1:  launch_variant<OP, 32, 4>(p, items, s); break;
+    case 2:  launch_variant<OP, 32, 5>(p, items, s); break;
+    case 3:  launch_variant<OP, 32, 3>(p, items, s); break;
+    default: launch_variant<OP, 64, 2>(p, items, s); break;
+  }
+}
+
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   BsParams p;
   p.dense_a = a.dense_a;  p.dense_b = a.dense_b;  p.sparse_in = a.sparse_in;
   p.out0 = a.out0;  p.out1 = a.out1;
   const dmoe_topology_t& t = *a.topo;
-  p.row_offsets = t.row_offsets;  p.column_indices = t.column_indices;  p.row_indices = t.row_indices;
+  p.row_offsets = t.row_offsets;  p.column_indices = t.column_indices;
   p.column_offsets_t = t.column_offsets_t;  p.row_indices_t = t.row_indices_t;  p.block_offsets_t = t.block_offsets_t;
-  p.counts = t.counts;  p.expert_order = t.expert_order;
+  p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;
+  { const char* e = getenv("DMOE_DBG"); p.dbg = e ? atoi(e) : 0; }
+  const int ncp = (p.hb + 1) / 2, njp = (p.db + 1) / 2;
+  const int g4 = ((a.g_max + 3) / 4) * 4;                 // majors are consumed in runs of 4
+  const int c4 = ((a.E * ncp + 3) / 4) * 4;
   switch (op) {
-    case OP_SDD:  hipLaunchKernelGGL(bsmm_kernel<OP_SDD>,  dim3(a.nnz_max), dim3(256), 0, s, p); break;
-    case OP_SDDT: hipLaunchKernelGGL(bsmm_kernel<OP_SDDT>, dim3(a.nnz_max), dim3(256), 0, s, p); break;
-    case OP_DSD:  hipLaunchKernelGGL(bsmm_kernel<OP_DSD>,  dim3(a.r_max * p.db), dim3(256), 0, s, p); break;
-    case OP_DSDT: hipLaunchKernelGGL(bsmm_kernel<OP_DSDT>, dim3(a.r_max * p.db), dim3(256), 0, s, p); break;
-    case OP_DSTD: hipLaunchKernelGGL(bsmm_kernel<OP_DSTD>, dim3(a.E * p.hb * p.db), dim3(256), 0, s, p); break;
-    case OP_DDTS: hipLaunchKernelGGL(bsmm_kernel<OP_DDTS>, dim3(a.E * p.hb * p.db), dim3(256), 0, s, p); break;
+    case OP_SDD:  launch_one<OP_SDD>(p, g4 * ncp, s); break;
+    case OP_SDDT: launch_one<OP_SDDT>(p, g4 * ncp, s); break;
+    case OP_DSD:  launch_one<OP_DSD>(p, g4 * njp, s); break;
+    case OP_DSDT: launch_one<OP_DSDT>(p, g4 * njp, s); break;
+    case OP_DSTD: launch_one<OP_DSTD>(p, c4 * njp, s); break;
+    case OP_DDTS: launch_one<OP_DDTS>(p, c4 * njp, s); break;
   }
 }
 

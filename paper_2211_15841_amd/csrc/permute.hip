@@ -1,6 +1,7 @@
 // Bandwidth-bound kernels around the block-sparse products: padded gather (Figure 6 step 3, Section 5.2),
 // weighted un-permute (step 5, Section 2.4), their backward counterparts, and the router's backward pass.
 #include "common.h"
+#include "mma_tile.h"
 
 namespace dmoe {
 
@@ -141,67 +142,184 @@ __global__ void __launch_bounds__(256) dlogits_kernel(const float* __restrict__ 
   }
 }
 
-// dx[t, i] = sum_s dXp[row_of[t,s], i] + sum_e dscores[t, e] * Wr[i, e].   Thread = hidden index i, workgroup =
-// 32 tokens x 256 hidden indices; dscores rows are broadcast from LDS.
-constexpr int kDxTok = 32;
-__global__ void __launch_bounds__(256) dx_kernel(const bf16_t* __restrict__ dxp, const int32_t* __restrict__ row_of,
-                                                 const float* __restrict__ dlogits, const bf16_t* __restrict__ wr,
-                                                 bf16_t* __restrict__ dx, int T, int d, int E, int k) {
-  extern __shared__ float dl_s[];           // [kDxTok][E]
-  const int t0 = blockIdx.x * kDxTok;
-  const int i = blockIdx.y * 256 + threadIdx.x;
-  const int nt = min(kDxTok, T - t0);
-  for (int q = threadIdx.x; q < nt * E; q += 256) dl_s[q] = dlogits[(size_t)t0 * E + q];
-  __syncthreads();
-  if (i >= d) return;
-  float acc[kDxTok];
+// Split an fp32 value into two bf16 values hi + lo (hi = nearest bf16, lo = nearest bf16 of the remainder), so that
+// a pair of bf16 MFMAs reproduces an fp32 operand to about 16 bits.
+__device__ __forceinline__ void split8(const float (&v)[8], bf16x8_v& hi, bf16x8_v& lo) {
+  union { uint32_t u[4]; bf16x8_v v; } h, l;
 #pragma unroll
-  for (int j = 0; j < kDxTok; ++j) acc[j] = 0.0f;
-  const bf16_t* wrow = wr + (size_t)i * E;
-  for (int e = 0; e < E; ++e) {
-    const float w = bf16_to_f32(wrow[e]);
-#pragma unroll
-    for (int j = 0; j < kDxTok; ++j)
-      if (j < nt) acc[j] = fmaf(dl_s[j * E + e], w, acc[j]);
+  for (int i = 0; i < 4; ++i) {
+    h.u[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
+    l.u[i] = pack_bf16(v[2 * i] - bf16_lo(h.u[i]), v[2 * i + 1] - bf16_hi(h.u[i]));
   }
+  hi = h.v;
+  lo = l.v;
+}
+
+// dx[t, i] = sum_s dXp[row_of[t,s], i] + sum_e dscores[t, e] * Wr[i, e].
+// A 128-token x 128-hidden tile per workgroup on MFMA with K = E; both operands have K contiguous in memory
+// (dscores [T,E], Wr [d,E]), so every lane loads its operand straight from global memory: no LDS.  The fp32
+// dscores are fed as a bf16 hi/lo pair.  The epilogue adds the un-permuted expert gradient rows and rounds to bf16.
+template <bool VEC>
+__global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__ dxp, const int32_t* __restrict__ row_of,
+                                                      const float* __restrict__ dlogits, const bf16_t* __restrict__ wr,
+                                                      bf16_t* __restrict__ dx, int T, int d, int E, int k) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * 128 + (wave >> 1) * 64;
+  const int i0 = blockIdx.y * 128 + (wave & 1) * 64;
+  f32x16_v acc[2][2];
 #pragma unroll
-  for (int j = 0; j < kDxTok; ++j) {
-    if (j < nt) {
-      const int t = t0 + j;
-      float v = acc[j];
-      for (int s = 0; s < k; ++s) v += bf16_to_f32(dxp[(size_t)row_of[t * k + s] * d + i]);
-      dx[(size_t)t * d + i] = (bf16_t)(pack_bf16(v, 0.0f) & 0xffffu);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+
+  for (int e0 = 0; e0 < E; e0 += 16) {
+    const int e = e0 + 8 * (lane >> 5);
+    bf16x8_v ah[2], al[2], bf[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int t = t0 + 32 * i + (lane & 31);
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = 0.0f;
+      if (t < T) {
+        const float* src = dlogits + (size_t)t * E + e;
+        if (VEC) {
+          if (e < E) {
+            const float4 p0 = *reinterpret_cast<const float4*>(src), p1 = *reinterpret_cast<const float4*>(src + 4);
+            v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) if (e + u < E) v[u] = src[u];
+        }
+      }
+      split8(v, ah[i], al[i]);
     }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const bf16_t* src = wr + (size_t)(i0 + 32 * j + (lane & 31)) * E + e;
+      union { uint4 q; bf16_t s[8]; bf16x8_v v; } w;
+      w.q = make_uint4(0, 0, 0, 0);
+      if (VEC) { if (e < E) w.q = *reinterpret_cast<const uint4*>(src); }
+      else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) if (e + u < E) w.s[u] = src[u];
+      }
+      bf[j] = w.v;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], ah[i], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], al[i], acc[i][j], 0, 0, 0);
+      }
+  }
+  // operands were swapped: lane l, register 4q+u of tile (i, j) is C[t0 + 32i + l%32][i0 + 32j + 8q + 4(l/32) + u]
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int t = t0 + 32 * i + (lane & 31);
+    if (t >= T) continue;
+    int rows[kMaxTopK];
+#pragma unroll
+    for (int s = 0; s < kMaxTopK; ++s) rows[s] = s < k ? row_of[(size_t)t * k + s] : 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = i0 + 32 * j + 8 * q + 4 * (lane >> 5);
+        float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+#pragma unroll
+        for (int s = 0; s < kMaxTopK; ++s) {
+          if (s < k) {
+            const uint2 g = *reinterpret_cast<const uint2*>(dxp + (size_t)rows[s] * d + n);
+            v0 += bf16_lo(g.x); v1 += bf16_hi(g.x); v2 += bf16_lo(g.y); v3 += bf16_hi(g.y);
+          }
+        }
+        uint2 o;
+        o.x = pack_bf16(v0, v1);  o.y = pack_bf16(v2, v3);
+        *reinterpret_cast<uint2*>(dx + (size_t)t * d + n) = o;
+      }
   }
 }
 
-// dWr[i, e] = sum_t x[t, i] * dscores[t, e]: per chunk of tokens into partials[chunk][i][e], then summed over
-// chunks in ascending order (deterministic).  Thread = (hidden index i, 16 experts).
-constexpr int kDwrTok = 64;
-constexpr int kDwrE = 16;
-__global__ void __launch_bounds__(256) dwr_partial_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dlogits,
-                                                          float* __restrict__ partials, int T, int d, int E) {
-  extern __shared__ float dl_s[];           // [kDwrTok][E]
-  const int chunk = blockIdx.x;
-  const int t0 = chunk * kDwrTok;
-  const int nt = min(kDwrTok, T - t0);
-  for (int q = threadIdx.x; q < nt * E; q += 256) dl_s[q] = dlogits[(size_t)t0 * E + q];
-  __syncthreads();
-  const int i = blockIdx.y * 256 + threadIdx.x;
-  if (i >= d) return;
-  for (int e0 = 0; e0 < E; e0 += kDwrE) {
-    float acc[kDwrE];
+// dWr[i, e] = sum_t x[t, i] * dscores[t, e].  Both operands have the reduction index t as their slow index, so both
+// are staged as [t][.] slabs and read with transposing LDS loads.  One workgroup = 128 hidden indices x up to 128
+// experts x a chunk of 256 tokens, written as an fp32 partial; the partials are then summed over chunks in
+// ascending order (deterministic).  dscores are fed as a bf16 hi/lo pair.
+constexpr int kDwrTok = 256;
+__global__ void __launch_bounds__(256) dwr_mfma_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dlogits,
+                                                       float* __restrict__ partials, int T, int d, int E) {
+  __shared__ __attribute__((aligned(16))) char xs[16384];
+  __shared__ __attribute__((aligned(16))) char hs[16384];
+  __shared__ __attribute__((aligned(16))) char ls[16384];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, i0 = blockIdx.y * 128, t0 = chunk * kDwrTok;
+
+  for (int eb = 0; eb < E; eb += 128) {
+    const int nsub = min(4, (E - eb + 31) / 32);
+    f32x16_v acc[4];
 #pragma unroll
-    for (int j = 0; j < kDwrE; ++j) acc[j] = 0.0f;
-    for (int t = 0; t < nt; ++t) {
-      const float xv = bf16_to_f32(x[(size_t)(t0 + t) * d + i]);
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int j = 0; j < kDwrE; ++j)
-        if (e0 + j < E) acc[j] = fmaf(xv, dl_s[t * E + e0 + j], acc[j]);
+      for (int q = 0; q < 16; ++q) acc[j][q] = 0.0f;
+
+    for (int kt = 0; kt < kDwrTok / 64; ++kt) {
+      const int tb = t0 + kt * 64;
+      if (tb >= T) break;
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int q = tid + 256 * r;
+        const int krow = q >> 4, c16 = q & 15;
+        const int t = tb + krow;
+        uint4 xv = make_uint4(0, 0, 0, 0);
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = 0.0f;
+        if (t < T) {
+          xv = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c16 * 8);
+          const int e = eb + c16 * 8;
+          const float* src = dlogits + (size_t)t * E + e;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) if (e + u < E) v[u] = src[u];
+        }
+        bf16x8_v hi, lo;
+        split8(v, hi, lo);
+        const int off = nc_offset(krow, c16);
+        *reinterpret_cast<uint4*>(xs + off) = xv;
+        *reinterpret_cast<bf16x8_v*>(hs + off) = hi;
+        *reinterpret_cast<bf16x8_v*>(ls + off) = lo;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8_v af = load_frag<NC, 64>(xs, 32 * wave, ks, lane);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (j < nsub) {
+            const bf16x8_v bh = load_frag<NC, 64>(hs, 32 * j, ks, lane);
+            const bf16x8_v bl = load_frag<NC, 64>(ls, 32 * j, ks, lane);
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bh, acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bl, acc[j], 0, 0, 0);
+          }
+        }
+      }
     }
+    // lane l, register r of tile j is C[i0 + 32 wave + 8 (r/4) + 4 (l/32) + r%4][eb + 32 j + l%32]
 #pragma unroll
-    for (int j = 0; j < kDwrE; ++j)
-      if (e0 + j < E) partials[((size_t)chunk * d + i) * E + e0 + j] = acc[j];
+    for (int j = 0; j < 4; ++j) {
+      const int e = eb + 32 * j + (lane & 31);
+      if (j < nsub && e < E) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = i0 + 32 * wave + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          partials[((size_t)chunk * d + row) * E + e] = acc[j][r];
+        }
+      }
+    }
   }
 }
 __global__ void __launch_bounds__(256) dwr_reduce_kernel(const float* __restrict__ partials, int nchunks, int n,
@@ -255,10 +373,13 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
     DMOE_DL_CASE(64)
   }
 #undef DMOE_DL_CASE
-  hipLaunchKernelGGL(dx_kernel, dim3((T + kDxTok - 1) / kDxTok, (d + 255) / 256), dim3(256),
-                     (size_t)kDxTok * E * sizeof(float), s, dxp, t.row_of, dlogits, wr, dx, T, d, E, k);
-  hipLaunchKernelGGL(dwr_partial_kernel, dim3(num_partials, (d + 255) / 256), dim3(256),
-                     (size_t)kDwrTok * E * sizeof(float), s, x, dlogits, partials, T, d, E);
+  if (E % 8 == 0)
+    hipLaunchKernelGGL(dx_mfma_kernel<true>, dim3((T + 127) / 128, d / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
+                       wr, dx, T, d, E, k);
+  else
+    hipLaunchKernelGGL(dx_mfma_kernel<false>, dim3((T + 127) / 128, d / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
+                       wr, dx, T, d, E, k);
+  hipLaunchKernelGGL(dwr_mfma_kernel, dim3(num_partials, d / 128), dim3(256), 0, s, x, dlogits, partials, T, d, E);
   hipLaunchKernelGGL(dwr_reduce_kernel, dim3((d * E + 255) / 256), dim3(256), 0, s, partials, num_partials, d * E,
                      dw_router);
 }

@@ -201,9 +201,11 @@ __global__ void __launch_bounds__(256) chunk_hist_kernel(const int32_t* __restri
 __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
                                                        int32_t* __restrict__ tokens_per_expert,
                                                        int32_t* __restrict__ padded_offsets, int32_t* __restrict__ counts,
-                                                       int32_t* __restrict__ expert_order) {
+                                                       int32_t* __restrict__ expert_order,
+                                                       int32_t* __restrict__ group_offsets) {
   __shared__ int n_s[kMaxExperts];
   __shared__ int scan_s[kMaxExperts];
+  __shared__ int gscan_s[kMaxExperts];
   const int tid = threadIdx.x;
   int n = 0;
   if (tid < E) {
@@ -217,15 +219,19 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
   const int padded = ((n + kBlock - 1) / kBlock) * kBlock;
   n_s[tid] = n;
   scan_s[tid] = tid < E ? padded : 0;
+  gscan_s[tid] = tid < E ? (padded / kBlock + 1) / 2 : 0;   // row groups: block-rows taken two at a time
   __syncthreads();
-  for (int off = 1; off < kMaxExperts; off <<= 1) {       // inclusive Hillis-Steele scan over experts
+  for (int off = 1; off < kMaxExperts; off <<= 1) {       // inclusive Hillis-Steele scans over experts
     const int add = tid >= off ? scan_s[tid - off] : 0;
+    const int gadd = tid >= off ? gscan_s[tid - off] : 0;
     __syncthreads();
     scan_s[tid] += add;
+    gscan_s[tid] += gadd;
     __syncthreads();
   }
-  if (tid < E) padded_offsets[tid + 1] = scan_s[tid];
+  if (tid < E) { padded_offsets[tid + 1] = scan_s[tid];  group_offsets[tid + 1] = gscan_s[tid]; }
   if (tid == 0) {
+    group_offsets[0] = 0;
     padded_offsets[0] = 0;
     const int P = scan_s[E - 1];
     counts[0] = P;
@@ -279,7 +285,8 @@ __global__ void __launch_bounds__(256) topology_kernel(const int32_t* __restrict
                                                        int32_t* __restrict__ row_offsets, int32_t* __restrict__ column_indices,
                                                        int32_t* __restrict__ row_indices, int32_t* __restrict__ column_offsets_t,
                                                        int32_t* __restrict__ row_indices_t, int32_t* __restrict__ block_offsets_t,
-                                                       int32_t* __restrict__ token_of) {
+                                                       int32_t* __restrict__ token_of, const int32_t* __restrict__ group_offsets,
+                                                       int32_t* __restrict__ row_group) {
   __shared__ int first_row[kMaxExperts + 1];
   for (int e = threadIdx.x; e <= E; e += 256) first_row[e] = padded_offsets[e] / kBlock;
   __syncthreads();
@@ -300,6 +307,11 @@ __global__ void __launch_bounds__(256) topology_kernel(const int32_t* __restrict
     block_offsets_t[idx] = (first_row[e] + jj) * hb + j;
   }
   if (idx <= R) row_offsets[idx] = idx * hb;
+  if (idx < R) {                           // row groups: rows 2i and 2i+1 of an expert share their column list
+    const int e = owner_of_block_row(first_row, E, idx);
+    const int local = idx - first_row[e];
+    if ((local & 1) == 0) row_group[group_offsets[e] + (local >> 1)] = idx * 2 + (idx + 1 < first_row[e + 1]);
+  }
   if (idx <= E * hb) {
     const int e = idx / hb, j = idx % hb;
     const int rows_e = e < E ? first_row[e + 1] - first_row[e] : 0;
@@ -364,7 +376,7 @@ void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_
   hipLaunchKernelGGL(chunk_hist_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts);
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kMaxExperts), 0, s, chunk_counts, nchunks, E, hb, t.tokens_per_expert,
-                     t.padded_offsets, t.counts, t.expert_order);
+                     t.padded_offsets, t.counts, t.expert_order, t.group_offsets);
   hipLaunchKernelGGL(rank_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts, t.padded_offsets, t.row_of, t.token_of);
 }
@@ -376,7 +388,7 @@ void launch_make_topology(const dmoe_config& c, const dmoe_topology_t& t, int p_
   if (p_max / kBlock + 1 > n) n = p_max / kBlock + 1;
   hipLaunchKernelGGL(topology_kernel, dim3((n + 255) / 256), dim3(256), 0, s, t.padded_offsets, t.tokens_per_expert,
                      c.num_experts, hb, t.row_offsets, t.column_indices, t.row_indices, t.column_offsets_t,
-                     t.row_indices_t, t.block_offsets_t, t.token_of);
+                     t.row_indices_t, t.block_offsets_t, t.token_of, t.group_offsets, t.row_group);
 }
 
 }  // namespace dmoe

@@ -68,6 +68,18 @@ def check_indices(gpu_topo: dict, ref: dict):
     order = gpu_topo["expert_order"]
     expect = sorted(range(len(n)), key=lambda e: (-int(n[e]), e))
     assert order.tolist() == expect
+    # row groups: every block-row appears exactly once, pairs never straddle two experts
+    first = np.asarray(ref["padded_offsets"], dtype=np.int64) // 128
+    goff, rg = gpu_topo["group_offsets"], gpu_topo["row_group"]
+    covered = []
+    for e in range(len(n)):
+        rows_e = int(first[e + 1] - first[e])
+        assert goff[e + 1] - goff[e] == (rows_e + 1) // 2
+        for j, v in enumerate(rg[goff[e]:goff[e + 1]]):
+            r0, two = int(v) >> 1, int(v) & 1
+            assert r0 == first[e] + 2 * j and two == (2 * j + 1 < rows_e)
+            covered += [r0] + ([r0 + 1] if two else [])
+    assert covered == list(range(int(first[-1]))) and len(rg) == goff[-1]
 
 
 def rel_err(g: np.ndarray, o: np.ndarray) -> float:
