@@ -279,53 +279,80 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
       }
     }
   }
+  __syncthreads();                                 // every wave is done with the operand stages: LDS is free
   if (!mine) return;
 
-  // ---- epilogue: lane l, accumulator register 4q+u of tile (i, jj) is
-  //      C[32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn)
+  // ---- epilogue.  Lane l, accumulator register 4q+u of tile (i, jj) is
+  //      C[32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn).
+  // Written straight from there, every store instruction would touch 32 rows with 16 bytes each; instead the
+  // wave's 128 x 64 tile is rounded to bf16 into a wave-private LDS tile (128-byte rows, chunk-swizzled like a KC
+  // slab) and written out as whole 128-byte row segments, 1 KB per store instruction.
+  char* ep = lds + wave * 16384;
   bf16_t* out;
   size_t ldo;
   size_t blk = 0;
   if constexpr (OP == OP_SDD || OP == OP_SDDT) {
-    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems;
+    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems + hn * 64;
     out = p.out0 + blk;  ldo = kBlock;
   } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-    out = p.out0 + (size_t)(pm ? r1 : r0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock;  ldo = d;
+    out = p.out0 + (size_t)(pm ? r1 : r0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock + hn * 64;  ldo = d;
   } else if constexpr (OP == OP_DSTD) {
-    out = p.out0 + (size_t)(pm ? c1 : c0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock;  ldo = d;
+    out = p.out0 + (size_t)(pm ? c1 : c0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock + hn * 64;  ldo = d;
   } else {
-    out = p.out0 + (size_t)(2 * jp + pm) * kBlock * ldw + (size_t)(pn ? c1 : c0) * kBlock;  ldo = ldw;
+    out = p.out0 + (size_t)(2 * jp + pm) * kBlock * ldw + (size_t)(pn ? c1 : c0) * kBlock + hn * 64;  ldo = ldw;
+  }
+  auto slot = [&](int i, int jj, int q) -> uint2* {          // this lane's 4 values of tile (i, jj), quad q
+    return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * i + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
+  };
+  auto flush = [&](bf16_t* dst) {                             // staging tile -> global, row-contiguous
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+      const uint4 v = *reinterpret_cast<const uint4*>(ep + kc_offset<64>(row, chunk));
+      *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
+    }
+  };
+  if constexpr (OP == OP_SDDT) {                              // global -> staging tile: H, for gelu'
+    const bf16_t* src = p.sparse_in + blk;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+      *reinterpret_cast<uint4*>(ep + kc_offset<64>(row, chunk)) =
+          *reinterpret_cast<const uint4*>(src + (size_t)row * ldo + chunk * 8);
+    }
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = 32 * i + (lane & 31);
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
+    for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = hn * 64 + 32 * jj + 8 * q + 4 * (lane >> 5);
         const float v0 = acc[i][jj][4 * q + 0], v1 = acc[i][jj][4 * q + 1];
         const float v2 = acc[i][jj][4 * q + 2], v3 = acc[i][jj][4 * q + 3];
-        const size_t o = (size_t)m * ldo + n;
-        if constexpr (OP == OP_SDD) {
-          uint2 hv, av;
-          hv.x = pack_bf16(v0, v1);  hv.y = pack_bf16(v2, v3);
-          av.x = pack_bf16(gelu_fwd(v0), gelu_fwd(v1));  av.y = pack_bf16(gelu_fwd(v2), gelu_fwd(v3));
-          *reinterpret_cast<uint2*>(out + o) = hv;
-          *reinterpret_cast<uint2*>(p.out1 + blk + o) = av;
-        } else if constexpr (OP == OP_SDDT) {
-          const uint2 hv = *reinterpret_cast<const uint2*>(p.sparse_in + blk + o);
-          uint2 gv;
-          gv.x = pack_bf16(v0 * gelu_bwd(bf16_lo(hv.x)), v1 * gelu_bwd(bf16_hi(hv.x)));
-          gv.y = pack_bf16(v2 * gelu_bwd(bf16_lo(hv.y)), v3 * gelu_bwd(bf16_hi(hv.y)));
-          *reinterpret_cast<uint2*>(out + o) = gv;
+        uint2 ov;
+        if constexpr (OP == OP_SDDT) {
+          const uint2 hv = *slot(i, jj, q);
+          ov.x = pack_bf16(v0 * gelu_bwd(bf16_lo(hv.x)), v1 * gelu_bwd(bf16_hi(hv.x)));
+          ov.y = pack_bf16(v2 * gelu_bwd(bf16_lo(hv.y)), v3 * gelu_bwd(bf16_hi(hv.y)));
         } else {
-          uint2 ov;
           ov.x = pack_bf16(v0, v1);  ov.y = pack_bf16(v2, v3);
-          *reinterpret_cast<uint2*>(out + o) = ov;
         }
+        *slot(i, jj, q) = ov;
       }
-    }
+  flush(out);
+  if constexpr (OP == OP_SDD) {                               // second output: A = gelu(H), from the fp32 values
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint2 av;
+          av.x = pack_bf16(gelu_fwd(acc[i][jj][4 * q + 0]), gelu_fwd(acc[i][jj][4 * q + 1]));
+          av.y = pack_bf16(gelu_fwd(acc[i][jj][4 * q + 2]), gelu_fwd(acc[i][jj][4 * q + 3]));
+          *slot(i, jj, q) = av;
+        }
+    flush(p.out1 + blk);
   }
 }
 
