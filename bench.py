@@ -196,6 +196,8 @@ def main():
     ap.add_argument("--also", default="small_zipf1.0,medium_zipf1.2_top2",
                     help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
@@ -209,6 +211,13 @@ def main():
 
     def pick(name):
         return CONFIGS[int(name) - 1] if name.isdigit() else CONFIG_BY_NAME[name]
+
+    if args.copy_calibration:      # a kernel whose HBM traffic is known: reads 1 GiB, writes 1 GiB
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)   # an elementwise kernel: distinct from the runtime's own copy kernels
+        torch.cuda.synchronize()
+        del src, dst
 
     hipev = HipEvents()
     cfg = pick(args.config)

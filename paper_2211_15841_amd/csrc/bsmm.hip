@@ -24,7 +24,6 @@
 // lie in memory with the transposing ds_read_b64_tr_b16; both are XOR-swizzled instead of padded.
 #include "common.h"
 #include "mma_tile.h"
-#include <cstdlib>
 
 namespace dmoe {
 
@@ -50,7 +49,6 @@ struct BsParams {
   const int32_t* row_group;
   const int32_t* expert_order;
   int d, h, E, hb, db;
-  int dbg;
 };
 
 template <int OP> struct OpLayouts;
@@ -120,9 +118,6 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
       c0 = p.column_indices[first0];
       c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
       nk = d / kBK;
-      if (p.dbg & 4) { r0 = r1 = 0; c0 = c1 = p.column_indices[0]; }   // experiment: every tile reads the same slabs
-      if (p.dbg & 8) { c0 = c1 = p.column_indices[0]; }
-      if (p.dbg & 16) { r0 = r1 = 0; }
     } else {
       jp = minor;
       b_ok[1] = 2 * jp + 1 < db;
@@ -252,7 +247,7 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
     if (kt + NS - 2 < nk) asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * kDmaPerTile) : "memory");
     else                  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                               // tile kt visible to all; everyone is done with tile kt-1
-    const bool more = kt + NS - 1 < nk && !(p.dbg & 2);
+    const bool more = kt + NS - 1 < nk;
     const int next_stage = (kt + NS - 1) % NS;
     if (more) slab_ptrs(kt + NS - 1);
     const char* sa = lds + (kt % NS) * kStageBytes + pm * kPanelBytes;
@@ -263,7 +258,7 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
       if (more && ks < 2) issue_loads(next_stage, ks);
-      if (mine && !(p.dbg & 1)) {
+      if (mine) {
         bf16x8_v af[4], bf[2];
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[i] = load_frag<LA, BK>(sa, 32 * i, ks, lane);
@@ -368,16 +363,11 @@ static void launch_variant(const BsParams& p, int items, hipStream_t s) {
   const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
   hipLaunchKernelGGL((bsmm_kernel<OP, BK, NS>), dim3(grid), dim3(kBsThreads), kLds, s, p);
 }
+// K = 64 per stage and two stages measured fastest on MI355X (K = 32 with three to five stages was 5-8% slower:
+// the products are bound by operand delivery, not by load latency, and shorter stages only add barriers).
 template <int OP>
 static void launch_one(const BsParams& p, int items, hipStream_t s) {
-  static int variant = -1;
-  if (variant < 0) { const char* e = getenv("DMOE_VARIANT"); variant = e ? atoi(e) : 0; }
-  switch (variant) {
-    case 1:  launch_variant<OP, 32, 4>(p, items, s); break;
-    case 2:  launch_variant<OP, 32, 5>(p, items, s); break;
-    case 3:  launch_variant<OP, 32, 3>(p, items, s); break;
-    default: launch_variant<OP, 64, 2>(p, items, s); break;
-  }
+  launch_variant<OP, 64, 2>(p, items, s);
 }
 
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
@@ -389,7 +379,6 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.column_offsets_t = t.column_offsets_t;  p.row_indices_t = t.row_indices_t;  p.block_offsets_t = t.block_offsets_t;
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;
-  { const char* e = getenv("DMOE_DBG"); p.dbg = e ? atoi(e) : 0; }
   const int ncp = (p.hb + 1) / 2, njp = (p.db + 1) / 2;
   const int g4 = ((a.g_max + 3) / 4) * 4;                 // majors are consumed in runs of 4
   const int c4 = ((a.E * ncp + 3) / 4) * 4;
