@@ -86,6 +86,9 @@ typedef struct {
   int32_t *group_offsets;      /* [E+1]     block-rows of an expert are taken two at a time ("row groups");
                                             first group of each expert, group_offsets[E] = number of groups      */
   int32_t *row_group;          /* [G_max]   2*(first block-row of the group) + (1 if the group has a second row) */
+  int32_t *sched;              /* [4]       sched[0] = 1 if the weight-gradient products should use 128x128 tiles
+                                            (one expert holds so many rows that its 256x256 tiles alone would
+                                            outlast a balanced schedule), else 0; rest reserved                  */
 } dmoe_topology_t;
 
 /* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,
@@ -141,6 +144,11 @@ DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out
 #define DMOE_STAGE_ROUTER_BWD   12   /* dlogits, dW_r, un-permute of dXp + router term (dmoe_backward) */
 #define DMOE_NUM_STAGES         13
 DMOE_API int dmoe_set_stage_events(void *events);
+
+/* Tile shape of the block-sparse products: 0 = chosen from the configuration (default), 1 = one 128x128 block per
+ * workgroup, 2 = 256x256 macro tiles (2x2 blocks).  Process-wide; results are identical, only speed differs.
+ * Meant for tests and tuning.                                                                                  */
+DMOE_API int dmoe_set_tile_mode(int mode);
 
 /* Message for the last error returned on this thread (host pointer to static thread-local storage). */
 DMOE_API const char *dmoe_last_error(void);

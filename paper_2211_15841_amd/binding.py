@@ -25,7 +25,7 @@ class DMoEConfig(ctypes.Structure):
 
 _TOPO_FIELDS = ["expert_idx", "weights", "logits", "tokens_per_expert", "padded_offsets", "row_of", "token_of",
                 "row_offsets", "column_indices", "row_indices", "column_offsets_t", "row_indices_t",
-                "block_offsets_t", "counts", "expert_order", "group_offsets", "row_group"]
+                "block_offsets_t", "counts", "expert_order", "group_offsets", "row_group", "sched"]
 
 
 class DMoETopology(ctypes.Structure):
@@ -61,9 +61,10 @@ def load_library() -> ctypes.CDLL:
                                   c_size_t, c_void_p]
     lib.dmoe_topology_counts_host.argtypes = [POINTER(DMoETopology), POINTER(c_int32), c_void_p]
     lib.dmoe_set_stage_events.argtypes = [c_void_p]
+    lib.dmoe_set_tile_mode.argtypes = [ctypes.c_int]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
-                 "dmoe_topology_counts_host", "dmoe_set_stage_events"):
+                 "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -127,6 +128,11 @@ def dmoe_topology_counts_host(topo, stream=None):
     out = (c_int32 * 4)()
     _check(load_library().dmoe_topology_counts_host(byref(topo), out, _stream(stream)))
     return list(out)
+
+
+def dmoe_set_tile_mode(mode: int):
+    """0: tile shape chosen from the configuration, 1: 128x128 blocks, 2: 256x256 macro tiles."""
+    _check(load_library().dmoe_set_tile_mode(mode))
 
 
 def dmoe_set_stage_events(events_array):
@@ -201,4 +207,5 @@ class Workspace:
             "expert_order": view("expert_order", E, i32),
             "group_offsets": view("group_offsets", E + 1, i32),
             "row_group": view("row_group", groups, i32),
+            "sched": view("sched", 4, i32),
         }

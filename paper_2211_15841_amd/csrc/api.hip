@@ -9,6 +9,7 @@ namespace dmoe {
 
 static thread_local char g_err[512] = "";
 static thread_local hipEvent_t* g_events = nullptr;
+static int g_force_tile = 0;
 
 static int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -57,11 +58,11 @@ static int check_config(const dmoe_config* c, Dims* out) {
 }
 
 struct TopoLayout {
-  size_t off[17];
+  size_t off[18];
   size_t total;
 };
 static TopoLayout topo_layout(const Dims& m) {
-  const size_t n[17] = {
+  const size_t n[18] = {
       (size_t)m.F * 4,             // expert_idx
       (size_t)m.F * 4,             // weights
       (size_t)m.T * m.E * 4,       // logits
@@ -79,10 +80,11 @@ static TopoLayout topo_layout(const Dims& m) {
       (size_t)m.E * 4,             // expert_order
       (size_t)(m.E + 1) * 4,       // group_offsets
       (size_t)(m.g_max + 1) * 4,   // row_group
+      16,                          // sched
   };
   TopoLayout l;
   size_t at = 0;
-  for (int i = 0; i < 17; ++i) { l.off[i] = at; at += align_up(n[i]); }
+  for (int i = 0; i < 18; ++i) { l.off[i] = at; at += align_up(n[i]); }
   l.total = at;
   return l;
 }
@@ -117,11 +119,11 @@ static int check_ptr(const void* p, const char* name) {
 }
 static int check_topo(const dmoe_topology_t* t) {
   if (!t) return fail(DMOE_EINVAL, "topology is NULL");
-  const void* ps[17] = {t->expert_idx, t->weights, t->logits, t->tokens_per_expert, t->padded_offsets, t->row_of,
+  const void* ps[18] = {t->expert_idx, t->weights, t->logits, t->tokens_per_expert, t->padded_offsets, t->row_of,
                         t->token_of, t->row_offsets, t->column_indices, t->row_indices, t->column_offsets_t,
                         t->row_indices_t, t->block_offsets_t, t->counts, t->expert_order, t->group_offsets,
-                        t->row_group};
-  for (int i = 0; i < 17; ++i)
+                        t->row_group, t->sched};
+  for (int i = 0; i < 18; ++i)
     if (!ps[i]) return fail(DMOE_EINVAL, "topology array %d is NULL (call dmoe_topology_bind first)", i);
   return DMOE_OK;
 }
@@ -174,6 +176,7 @@ int dmoe_topology_bind(const dmoe_config* cfg, void* topology_mem, size_t bytes,
   out->expert_order = reinterpret_cast<int32_t*>(b + l.off[14]);
   out->group_offsets = reinterpret_cast<int32_t*>(b + l.off[15]);
   out->row_group = reinterpret_cast<int32_t*>(b + l.off[16]);
+  out->sched = reinterpret_cast<int32_t*>(b + l.off[17]);
   return DMOE_OK;
 }
 
@@ -229,7 +232,8 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
   ev.end(DMOE_STAGE_GATHER);
 
   BsArgs a{};
-  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max;
+  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max; a.r_max = m.r_max;
+  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
   ev.begin(DMOE_STAGE_SDD);
   a.dense_a = xp; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = nullptr; a.out0 = hval; a.out1 = aval;
   launch_bsmm(OP_SDD, a, s);
@@ -288,7 +292,8 @@ int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, c
   ev.end(DMOE_STAGE_BWD_GATHER);
 
   BsArgs a{};
-  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max;
+  a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max; a.r_max = m.r_max;
+  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
 
   ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * gelu'(H)
   a.dense_a = dyp; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = hval; a.out0 = dh; a.out1 = nullptr;
@@ -328,6 +333,12 @@ int dmoe_topology_counts_host(const dmoe_topology_t* topo, int32_t* out4, void* 
 
 int dmoe_set_stage_events(void* events) {
   g_events = static_cast<hipEvent_t*>(events);
+  return DMOE_OK;
+}
+
+int dmoe_set_tile_mode(int mode) {
+  if (mode < 0 || mode > 2) return fail(DMOE_EINVAL, "tile mode must be 0 (automatic), 1 (128x128) or 2 (256x256)");
+  g_force_tile = mode;
   return DMOE_OK;
 }
 

@@ -48,7 +48,10 @@ struct BsParams {
   const int32_t* group_offsets;
   const int32_t* row_group;
   const int32_t* expert_order;
+  const int32_t* counts;
+  const int32_t* sched;
   int d, h, E, hb, db;
+  int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
 };
 
 template <int OP> struct OpLayouts;
@@ -67,78 +70,94 @@ __device__ __forceinline__ int patch_item(int wg) {
   return ((slot / kPatch) * 8 + xcd) * kPatch + slot % kPatch;
 }
 
-template <int OP, int BK, int NS>
-__global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
+// PAN = panels per operand: 2 -> the 256x256 macro tile (each wave 128x64), 1 -> a single 128x128 block shared by the
+// eight waves (each wave 32x64).  The small tile has half the arithmetic intensity but four times as many work items,
+// a 32 KB stage (so five stages fit in LDS) and is what the HBM-bound and the few-tiles-per-expert cases want.
+template <int OP, int PAN, int NS>
+__global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
-  constexpr int kBK = BK;
+  constexpr int BK = 64;                            // K per pipeline stage
   constexpr int kSub = kBlock / BK;                 // K tiles per 128-wide sparse block
-  constexpr int kSubShift = BK == 64 ? 1 : 2;
-  constexpr int kPanelBytes = 256 * BK;
-  constexpr int kStageBytes = 4 * kPanelBytes;
+  constexpr int kPanelBytes = 256 * BK;             // one 128 x 64 bf16 slab, either way round
+  constexpr int kStageBytes = 2 * PAN * kPanelBytes;
   constexpr int kCpw = kPanelBytes / 8192;          // 1 KB DMA chunks per wave per slab
-  constexpr int kDmaPerTile = 4 * kCpw;             // DMA instructions per wave per K tile
-  extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A0 A1 B0 B1][slab]
+  constexpr int kDmaPerTile = 2 * PAN * kCpw;       // DMA instructions per wave per K tile
+  constexpr int MI = PAN == 2 ? 4 : 1;              // 32-row MFMA tiles per wave (the wave is always 64 columns wide)
+  constexpr bool kSparseOut = OP == OP_SDD || OP == OP_SDDT;
+  constexpr bool kRowMajor = kSparseOut || OP == OP_DSD || OP == OP_DSDT;   // items enumerate block rows
+  extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A slabs, B slabs]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int pm = wave >> 2, pn = (wave >> 1) & 1, hn = wave & 1;
+  const int pm = PAN == 2 ? wave >> 2 : 0;          // A panel / B panel of this wave
+  const int pn = PAN == 2 ? (wave >> 1) & 1 : 0;
+  const int arow0 = PAN == 2 ? 0 : (wave >> 1) * 32;  // first row of the wave inside its A panel
+  const int hn = wave & 1;                          // which 64-column half of the B panel
   const int d = p.d, hb = p.hb, db = p.db;
-  const size_t ldw = (size_t)p.E * p.h;            // leading dimension of W1 / dW1
-  const int ncp = (hb + 1) >> 1, njp = (db + 1) >> 1;
+  const size_t ldw = (size_t)p.E * p.h;             // leading dimension of W1 / dW1
+  const int ncu = (hb + PAN - 1) / PAN, nju = (db + PAN - 1) / PAN;   // column units / d units per row
 
-  // ---- which macro tile --------------------------------------------------------------------------------------
-  // Items are numbered so that 4 consecutive "major" indices (row groups / column pairs) times all "minor"
-  // indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
+  // ---- which tile ------------------------------------------------------------------------------------------
+  // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
+  // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
   const int item = patch_item(blockIdx.x);
   int major, minor;
   {
-    const int nminor = (OP == OP_SDD || OP == OP_SDDT) ? ncp : njp;
+    const int nminor = kSparseOut ? ncu : nju;
     const int run = item / (4 * nminor), rem = item % (4 * nminor);
     major = run * 4 + (rem & 3);
     minor = rem >> 2;
   }
   bool a_ok[2] = {true, false}, b_ok[2] = {true, false};
   int nk = 0;
-  int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jp = 0;
-  if constexpr (OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT) {
-    const int G = p.group_offsets[p.E];
-    if (major >= G) return;
-    const int rg = p.row_group[major];             // first block-row * 2 + (group has a second row)
-    r0 = rg >> 1;
-    a_ok[1] = rg & 1;
+  int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jd0 = 0;
+  if constexpr (kRowMajor) {
+    if constexpr (PAN == 2) {
+      if (major >= p.group_offsets[p.E]) return;
+      const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
+      r0 = rg >> 1;
+      a_ok[1] = rg & 1;
+    } else {
+      if (major >= p.counts[1]) return;
+      r0 = major;
+    }
     r1 = a_ok[1] ? r0 + 1 : r0;
     first0 = p.row_offsets[r0];
     first1 = p.row_offsets[r1];
     const int nblk = p.row_offsets[r0 + 1] - first0;
-    if constexpr (OP == OP_SDD || OP == OP_SDDT) {
-      if (2 * minor >= nblk) return;
-      b_ok[1] = 2 * minor + 1 < nblk;
-      first0 += 2 * minor;                         // block (r0, c0); (r0, c1) is the next one
-      first1 += 2 * minor;
+    if constexpr (kSparseOut) {
+      if (PAN * minor >= nblk) return;
+      b_ok[1] = PAN == 2 && 2 * minor + 1 < nblk;
+      first0 += PAN * minor;                        // block (r0, c0); (r0, c1) is the next one
+      first1 += PAN * minor;
       c0 = p.column_indices[first0];
       c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
-      nk = d / kBK;
+      nk = d / BK;
     } else {
-      jp = minor;
-      b_ok[1] = 2 * jp + 1 < db;
+      jd0 = PAN * minor;
+      b_ok[1] = PAN == 2 && jd0 + 1 < db;
       nk = kSub * nblk;
     }
   } else {
-    if (major >= p.E * ncp) return;
-    const int e = p.expert_order[major / ncp];     // heaviest experts first
-    const int cp = major % ncp;
-    jp = minor;
-    c0 = e * hb + 2 * cp;
-    const bool second_col = 2 * cp + 1 < hb;
+    // Both tile shapes are launched for the weight gradients; the routing decides on the device which one works.
+    const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
+    if (want_small != (PAN == 1 ? 1 : 0)) return;
+    if (major >= p.E * ncu) return;
+    const int e = p.expert_order[major / ncu];      // heaviest experts first
+    const int cu = major % ncu;
+    jd0 = PAN * minor;
+    c0 = e * hb + PAN * cu;
+    const bool second_col = PAN == 2 && 2 * cu + 1 < hb;
+    const bool second_d = PAN == 2 && jd0 + 1 < db;
     c1 = second_col ? c0 + 1 : c0;
     first0 = p.column_offsets_t[c0];
     first1 = p.column_offsets_t[c1];
     nk = kSub * (p.column_offsets_t[c0 + 1] - first0);
-    if constexpr (OP == OP_DSTD) { a_ok[1] = second_col;  b_ok[1] = 2 * jp + 1 < db; }
-    else                         { a_ok[1] = 2 * jp + 1 < db;  b_ok[1] = second_col; }
+    if constexpr (OP == OP_DSTD) { a_ok[1] = second_col;  b_ok[1] = second_d; }
+    else                         { a_ok[1] = second_d;    b_ok[1] = second_col; }
   }
 
-  // ---- per-K-tile slab base pointers (wave-uniform) ----------------------------------------------------------
+  // ---- per-K-tile slab base pointers (wave-uniform) --------------------------------------------------------
   const bf16_t *a0, *a1, *b0, *b1;
   uint32_t lda, ldb;
   if constexpr (OP == OP_SDD)       { lda = d;      ldb = (uint32_t)ldw; }
@@ -150,51 +169,50 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
 
   auto slab_ptrs = [&](int kt) {
     if constexpr (OP == OP_SDD) {
-      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * kBK;
-      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * kBK;
-      b0 = p.dense_b + (size_t)kt * kBK * ldw + (size_t)c0 * kBlock;
-      b1 = p.dense_b + (size_t)kt * kBK * ldw + (size_t)c1 * kBlock;
+      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * BK;
+      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * BK;
+      b0 = p.dense_b + (size_t)kt * BK * ldw + (size_t)c0 * kBlock;
+      b1 = p.dense_b + (size_t)kt * BK * ldw + (size_t)c1 * kBlock;
     } else if constexpr (OP == OP_SDDT) {
-      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * kBK;
-      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * kBK;
-      b0 = p.dense_b + (size_t)c0 * kBlock * d + kt * kBK;
-      b1 = p.dense_b + (size_t)c1 * kBlock * d + kt * kBK;
+      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * BK;
+      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * BK;
+      b0 = p.dense_b + (size_t)c0 * kBlock * d + kt * BK;
+      b1 = p.dense_b + (size_t)c1 * kBlock * d + kt * BK;
     } else if constexpr (OP == OP_DSD) {
-      const int kb = kt >> kSubShift, half = kt & (kSub - 1);
+      const int kb = kt / kSub, half = kt % kSub;
       const int col = p.column_indices[first0 + kb];
-      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * kBK;
-      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * kBK;
-      b0 = p.dense_b + ((size_t)col * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
+      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
+      b0 = p.dense_b + ((size_t)col * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else if constexpr (OP == OP_DSDT) {
-      const int kb = kt >> kSubShift, half = kt & (kSub - 1);
+      const int kb = kt / kSub, half = kt % kSub;
       const int col = p.column_indices[first0 + kb];
-      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * kBK;
-      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * kBK;
-      b0 = p.dense_b + (size_t)(2 * jp) * kBlock * ldw + (size_t)col * kBlock + half * kBK;
+      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
+      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
+      b0 = p.dense_b + (size_t)jd0 * kBlock * ldw + (size_t)col * kBlock + half * BK;
       b1 = b0 + (b_ok[1] ? (size_t)kBlock * ldw : 0);
     } else if constexpr (OP == OP_DSTD) {
-      const int i = kt >> kSubShift, half = kt & (kSub - 1);
+      const int i = kt / kSub, half = kt % kSub;
       const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
       const int row = p.row_indices_t[first0 + i];
-      a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * kBK * kBlock;
-      a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * kBK * kBlock;
-      b0 = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
+      a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
+      b0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else {  // OP_DDTS
-      const int i = kt >> kSubShift, half = kt & (kSub - 1);
+      const int i = kt / kSub, half = kt % kSub;
       const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
       const int row = p.row_indices_t[first0 + i];
-      a0 = p.dense_a + ((size_t)row * kBlock + half * kBK) * d + (size_t)(2 * jp) * kBlock;
+      a0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       a1 = a0 + (a_ok[1] ? kBlock : 0);
-      b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * kBK * kBlock;
-      b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * kBK * kBlock;
+      b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
+      b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
     }
   };
 
-  // Each wave moves 1 KB chunk `wave` (and `wave + 8` when a slab has 16 of them) of every slab.  All four slabs are
-  // always loaded, a missing panel re-reads its sibling: the number of loads per K tile must be a constant for the
-  // counted waits below.
+  // Each wave moves 1 KB chunks `wave` and `wave + 8` of every slab.  All slabs are always loaded (a missing panel
+  // re-reads its sibling): the number of loads per K tile must be a constant for the counted waits below.
   uint32_t oa[kCpw], ob[kCpw];
 #pragma unroll
   for (int i = 0; i < kCpw; ++i) {
@@ -208,30 +226,30 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   auto dma16 = [](const bf16_t* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory");
   };
-  // part 0 = the two A slabs, part 1 = the two B slabs (issued at different points of the MFMA loop, see below)
+  // part 0 = the A slabs, part 1 = the B slabs (issued at different points of the MFMA loop, see below)
   auto issue_loads = [&](int stage, int part) {
     const uint32_t s = __builtin_amdgcn_readfirstlane(lds_base + stage * kStageBytes + wave * 1024);
 #pragma unroll
     for (int i = 0; i < kCpw; ++i) {
       if (part == 0) {
         dma16(a0 + oa[i], s + 8192 * i);
-        dma16(a1 + oa[i], s + kPanelBytes + 8192 * i);
+        if (PAN == 2) dma16(a1 + oa[i], s + kPanelBytes + 8192 * i);
       } else {
-        dma16(b0 + ob[i], s + 2 * kPanelBytes + 8192 * i);
-        dma16(b1 + ob[i], s + 3 * kPanelBytes + 8192 * i);
+        dma16(b0 + ob[i], s + PAN * kPanelBytes + 8192 * i);
+        if (PAN == 2) dma16(b1 + ob[i], s + (PAN + 1) * kPanelBytes + 8192 * i);
       }
     }
   };
 
-  f32x16_v acc[4][2];
+  f32x16_v acc[MI][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][jj][q] = 0.0f;
 
-  const bool mine = a_ok[pm] && b_ok[pn];          // this wave's quadrant exists
+  const bool mine = a_ok[pm] && b_ok[pn];          // this wave's part of the tile exists
   // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
   // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
   // t has landed; near the end of K, when fewer tiles are in flight, the wait is for everything.
@@ -251,23 +269,22 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
     const int next_stage = (kt + NS - 1) % NS;
     if (more) slab_ptrs(kt + NS - 1);
     const char* sa = lds + (kt % NS) * kStageBytes + pm * kPanelBytes;
-    const char* sb = lds + (kt % NS) * kStageBytes + (2 + pn) * kPanelBytes;
+    const char* sb = lds + (kt % NS) * kStageBytes + (PAN + pn) * kPanelBytes;
     // The loads of the next tile are spread over the first two K steps instead of being issued in one burst: a
-    // wave cannot start its MFMAs before its own loads have been issued, and 64 back-to-back 1 KB loads keep the
-    // CU's address unit busy for about a thousand cycles.
+    // wave cannot start its MFMAs before its own loads have been issued.
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
+    for (int ks = 0; ks < BK / 16; ++ks) {
       if (more && ks < 2) issue_loads(next_stage, ks);
       if (mine) {
-        bf16x8_v af[4], bf[2];
+        bf16x8_v af[MI], bf[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = load_frag<LA, BK>(sa, 32 * i, ks, lane);
+        for (int i = 0; i < MI; ++i) af[i] = load_frag<LA, BK>(sa, arow0 + 32 * i, ks, lane);
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) bf[jj] = load_frag<LB, BK>(sb, hn * 64 + 32 * jj, ks, lane);
         // Operands swapped on purpose: the MFMA "row" index runs over n and the "column" index over m, so each
         // lane ends up with four consecutive n of one output row and can store them as one 8-byte word.
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int jj = 0; jj < 2; ++jj)
             acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[jj], af[i], acc[i][jj], 0, 0, 0);
@@ -278,30 +295,30 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   if (!mine) return;
 
   // ---- epilogue.  Lane l, accumulator register 4q+u of tile (i, jj) is
-  //      C[32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn).
+  //      C[arow0 + 32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn).
   // Written straight from there, every store instruction would touch 32 rows with 16 bytes each; instead the
-  // wave's 128 x 64 tile is rounded to bf16 into a wave-private LDS tile (128-byte rows, chunk-swizzled like a KC
-  // slab) and written out as whole 128-byte row segments, 1 KB per store instruction.
-  char* ep = lds + wave * 16384;
+  // wave's (32 MI) x 64 tile is rounded to bf16 into a wave-private LDS tile (128-byte rows, chunk-swizzled like a
+  // KC slab) and written out as whole 128-byte row segments, 1 KB per store instruction.
+  char* ep = lds + wave * (MI * 4096);
   bf16_t* out;
   size_t ldo;
   size_t blk = 0;
-  if constexpr (OP == OP_SDD || OP == OP_SDDT) {
-    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems + hn * 64;
+  if constexpr (kSparseOut) {
+    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems + (size_t)arow0 * kBlock + hn * 64;
     out = p.out0 + blk;  ldo = kBlock;
   } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-    out = p.out0 + (size_t)(pm ? r1 : r0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock + hn * 64;  ldo = d;
+    out = p.out0 + ((size_t)(pm ? r1 : r0) * kBlock + arow0) * d + (size_t)(jd0 + pn) * kBlock + hn * 64;  ldo = d;
   } else if constexpr (OP == OP_DSTD) {
-    out = p.out0 + (size_t)(pm ? c1 : c0) * kBlock * d + (size_t)(2 * jp + pn) * kBlock + hn * 64;  ldo = d;
+    out = p.out0 + ((size_t)(pm ? c1 : c0) * kBlock + arow0) * d + (size_t)(jd0 + pn) * kBlock + hn * 64;  ldo = d;
   } else {
-    out = p.out0 + (size_t)(2 * jp + pm) * kBlock * ldw + (size_t)(pn ? c1 : c0) * kBlock + hn * 64;  ldo = ldw;
+    out = p.out0 + ((size_t)(jd0 + pm) * kBlock + arow0) * ldw + (size_t)(pn ? c1 : c0) * kBlock + hn * 64;  ldo = ldw;
   }
   auto slot = [&](int i, int jj, int q) -> uint2* {          // this lane's 4 values of tile (i, jj), quad q
     return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * i + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
   };
   auto flush = [&](bf16_t* dst) {                             // staging tile -> global, row-contiguous
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < 4 * MI; ++it) {
       const int row = 8 * it + (lane >> 3), chunk = lane & 7;
       const uint4 v = *reinterpret_cast<const uint4*>(ep + kc_offset<64>(row, chunk));
       *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
@@ -310,14 +327,14 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   if constexpr (OP == OP_SDDT) {                              // global -> staging tile: H, for gelu'
     const bf16_t* src = p.sparse_in + blk;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < 4 * MI; ++it) {
       const int row = 8 * it + (lane >> 3), chunk = lane & 7;
       *reinterpret_cast<uint4*>(ep + kc_offset<64>(row, chunk)) =
           *reinterpret_cast<const uint4*>(src + (size_t)row * ldo + chunk * 8);
     }
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -337,7 +354,7 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   flush(out);
   if constexpr (OP == OP_SDD) {                               // second output: A = gelu(H), from the fp32 values
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -351,23 +368,43 @@ __global__ void __launch_bounds__(kBsThreads, 2) bsmm_kernel(const BsParams p) {
   }
 }
 
-template <int OP, int BK, int NS>
-static void launch_variant(const BsParams& p, int items, hipStream_t s) {
+template <int OP, int PAN, int NS>
+static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
   static bool configured = false;
-  constexpr int kLds = NS * 4 * 256 * BK;
+  constexpr int kLds = NS * 2 * PAN * 16384;
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, BK, NS>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PAN, NS>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     configured = true;
   }
+  const int items = ((majors + 3) / 4) * 4 * nminor;          // majors are consumed in runs of 4
   const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
-  hipLaunchKernelGGL((bsmm_kernel<OP, BK, NS>), dim3(grid), dim3(kBsThreads), kLds, s, p);
+  hipLaunchKernelGGL((bsmm_kernel<OP, PAN, NS>), dim3(grid), dim3(kBsThreads), kLds, s, p);
 }
-// K = 64 per stage and two stages measured fastest on MI355X (K = 32 with three to five stages was 5-8% slower:
-// the products are bound by operand delivery, not by load latency, and shorter stages only add barriers).
+
+// Tile choice (host side, from the configuration only -- the routing is not known to the host):
+//  * 256x256 macro tiles, two LDS stages: when there are enough of them to fill 256 CUs a few times over; they halve
+//    the L2->LDS traffic per flop, which is what bounds the MFMA-bound configurations.
+//  * single 128x128 blocks, two or more workgroups per CU: when the big tiles would be too few to fill the machine
+//    (small T*k).  For the weight gradients the same question depends on the routing (one popular expert owns few
+//    big tiles with a very long K), so both shapes are launched and a flag computed on the device picks one.
 template <int OP>
-static void launch_one(const BsParams& p, int items, hipStream_t s) {
-  launch_variant<OP, 64, 2>(p, items, s);
+static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
+  const int hb = p.hb, db = p.db;
+  const bool row_major = OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT;
+  const bool sparse_out = OP == OP_SDD || OP == OP_SDDT;
+  const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
+  if (row_major) {
+    bool small = (long long)a.groups_est * big_minor < 256 + (sparse_out ? 1 : 0);
+    if (a.force_tile == 1) small = true;
+    if (a.force_tile == 2) small = false;
+    if (small) launch_variant<OP, 1, 2>(p, a.r_max, sparse_out ? hb : db, s);
+    else       launch_variant<OP, 2, 2>(p, a.g_max, big_minor, s);
+  } else {
+    // the device-side flag sched[0] selects which of the two launches does the work (the other exits at once)
+    launch_variant<OP, 2, 2>(p, a.E * ((hb + 1) / 2), big_minor, s);
+    launch_variant<OP, 1, 2>(p, a.E * hb, db, s);
+  }
 }
 
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
@@ -378,17 +415,15 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.row_offsets = t.row_offsets;  p.column_indices = t.column_indices;
   p.column_offsets_t = t.column_offsets_t;  p.row_indices_t = t.row_indices_t;  p.block_offsets_t = t.block_offsets_t;
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
-  p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;
-  const int ncp = (p.hb + 1) / 2, njp = (p.db + 1) / 2;
-  const int g4 = ((a.g_max + 3) / 4) * 4;                 // majors are consumed in runs of 4
-  const int c4 = ((a.E * ncp + 3) / 4) * 4;
+  p.counts = t.counts;  p.sched = t.sched;
+  p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   switch (op) {
-    case OP_SDD:  launch_one<OP_SDD>(p, g4 * ncp, s); break;
-    case OP_SDDT: launch_one<OP_SDDT>(p, g4 * ncp, s); break;
-    case OP_DSD:  launch_one<OP_DSD>(p, g4 * njp, s); break;
-    case OP_DSDT: launch_one<OP_DSDT>(p, g4 * njp, s); break;
-    case OP_DSTD: launch_one<OP_DSTD>(p, c4 * njp, s); break;
-    case OP_DDTS: launch_one<OP_DDTS>(p, c4 * njp, s); break;
+    case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;
+    case OP_SDDT: launch_one<OP_SDDT>(p, a, s); break;
+    case OP_DSD:  launch_one<OP_DSD>(p, a, s); break;
+    case OP_DSDT: launch_one<OP_DSDT>(p, a, s); break;
+    case OP_DSTD: launch_one<OP_DSTD>(p, a, s); break;
+    case OP_DDTS: launch_one<OP_DDTS>(p, a, s); break;
   }
 }
 

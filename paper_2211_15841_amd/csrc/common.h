@@ -87,7 +87,10 @@ int router_bwd_num_partials(const dmoe_config& c);
 enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5 };
 struct BsArgs {
   const dmoe_topology_t* topo;
-  int d, h, E, g_max;      // g_max: upper bound on the number of row groups
+  int d, h, E;
+  int g_max, r_max;        // upper bounds on the number of row groups / block rows
+  int groups_est;          // T*k/256: row groups if the routing were perfectly packed (tile-size heuristic)
+  int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: H for gelu')

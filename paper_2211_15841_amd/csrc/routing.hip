@@ -199,6 +199,7 @@ __global__ void __launch_bounds__(256) chunk_hist_kernel(const int32_t* __restri
 // Single workgroup.  Turns chunk_counts into exclusive per-expert bases (in place), and writes
 // tokens_per_expert, padded_offsets (rows per expert = ceil(n_e/128)*128, Section 5.2), counts and expert_order.
 __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
+                                                              int db, int32_t* __restrict__ sched,
                                                        int32_t* __restrict__ tokens_per_expert,
                                                        int32_t* __restrict__ padded_offsets, int32_t* __restrict__ counts,
                                                        int32_t* __restrict__ expert_order,
@@ -238,6 +239,15 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
     counts[1] = P / kBlock;
     counts[2] = (P / kBlock) * hb;
     counts[3] = 0;
+    // Weight-gradient schedule.  With 256x256 macro tiles an expert owns ceil(hb/2)*ceil(db/2) tiles whose K is its
+    // row count; a balanced schedule gives each of the 256 CUs R * tiles / 256 block-steps.  When the most loaded
+    // expert's own tiles are much longer than that, the machine would idle behind them: use 128x128 tiles then.
+    int max_rows = 0;
+    for (int e = 0; e < E; ++e) max_rows = max(max_rows, (n_s[e] + kBlock - 1) / kBlock);
+    const long long tiles = (long long)((hb + 1) / 2) * ((db + 1) / 2);
+    const long long share = (long long)(P / kBlock) * tiles / 256;
+    sched[0] = (2LL * max_rows > 3 * share && tiles < 256) ? 1 : 0;
+    sched[1] = sched[2] = sched[3] = 0;
   }
   if (tid < E) {                                           // position of expert `tid` in descending-load order
     int pos = 0;
@@ -375,7 +385,8 @@ void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_
   const int hb = c.ffn_hidden / kBlock;
   hipLaunchKernelGGL(chunk_hist_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts);
-  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kMaxExperts), 0, s, chunk_counts, nchunks, E, hb, t.tokens_per_expert,
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kMaxExperts), 0, s, chunk_counts, nchunks, E, hb,
+                     c.d_model / kBlock, t.sched, t.tokens_per_expert,
                      t.padded_offsets, t.counts, t.expert_order, t.group_offsets);
   hipLaunchKernelGGL(rank_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts, t.padded_offsets, t.row_of, t.token_of);

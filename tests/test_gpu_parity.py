@@ -87,3 +87,18 @@ def test_two_runs_are_bitwise_identical():
         assert np.array_equal(a[key], b[key]), key
     for key, val in a["topo"].items():
         assert np.array_equal(val, b["topo"][key]), key
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["tiles_128", "tiles_256"])
+def test_both_tile_shapes_give_the_same_answers(mode):
+    """The block-sparse products have a 128x128 and a 256x256 tiling; force each one on cases with odd block counts,
+    empty experts and a dominant expert (the automatic choice is covered by every other test)."""
+    import paper_2211_15841_amd as dm
+    dm.dmoe_set_tile_mode(mode)
+    try:
+        for cfg in (small_config("odd_blocks", T=700, d=384, h=640, E=6, k=2, normalize_topk=1, zipf_s=1.5, seed=121),
+                    small_config("dominant", T=2000, d=256, h=256, E=8, k=1, zipf_s=3.0, seed=122),
+                    CONFIGS[0]):
+            full_parity(cfg)
+    finally:
+        dm.dmoe_set_tile_mode(0)
