@@ -70,32 +70,42 @@ __device__ __forceinline__ int patch_item(int wg) {
   return ((slot / kPatch) * 8 + xcd) * kPatch + slot % kPatch;
 }
 
-// PAN = panels per operand: 2 -> the 256x256 macro tile (each wave 128x64), 1 -> a single 128x128 block shared by the
-// eight waves (each wave 32x64).  The small tile has half the arithmetic intensity but four times as many work items,
-// a 32 KB stage (so five stages fit in LDS) and is what the HBM-bound and the few-tiles-per-expert cases want.
-template <int OP, int PAN, int NS>
-__global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(const BsParams p) {
+// PA, PB = number of 128-row A panels and 128-column B panels of the tile:
+//   2,2 -> the 256x256 macro tile (each of 8 waves 128x64; or 16 waves of 64x64), two LDS stages;
+//   2,1 -> 256x128 (each wave 64x64), three LDS stages;
+//   1,1 -> a single 128x128 block shared by eight waves (32x64 each), two or more workgroups per CU: half the
+//          arithmetic intensity but four times as many work items, for under-filled launches.
+template <int OP, int PA, int PB, int NS, int NW>
+__global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
   constexpr int BK = 64;                            // K per pipeline stage
   constexpr int kSub = kBlock / BK;                 // K tiles per 128-wide sparse block
   constexpr int kPanelBytes = 256 * BK;             // one 128 x 64 bf16 slab, either way round
-  constexpr int kStageBytes = 2 * PAN * kPanelBytes;
-  constexpr int kCpw = kPanelBytes / 8192;          // 1 KB DMA chunks per wave per slab
-  constexpr int kDmaPerTile = 2 * PAN * kCpw;       // DMA instructions per wave per K tile
-  constexpr int MI = PAN == 2 ? 4 : 1;              // 32-row MFMA tiles per wave (the wave is always 64 columns wide)
+  constexpr int kStageBytes = (PA + PB) * kPanelBytes;
+  constexpr int kCpw = 16 / NW;                     // 1 KB DMA chunks per wave per slab (a slab has 16)
+  constexpr int kDmaPerTile = (PA + PB) * kCpw;     // DMA instructions per wave per K tile
+  // 32-row MFMA tiles per wave (a wave is always 64 columns wide): 8 waves on 2x2 blocks -> 128x64 per wave,
+  // 16 waves on 2x2 blocks -> 64x64 per wave (four waves per SIMD), 8 waves on one block -> 32x64 per wave.
+  constexpr int WB = NW / (PA * PB);                // waves per 128x128 block of the tile
+  constexpr int MI = 8 / WB;
+  static_assert(WB == 2 || WB == 4 || WB == 8, "unsupported tile / workgroup shape");
   constexpr bool kSparseOut = OP == OP_SDD || OP == OP_SDDT;
   constexpr bool kRowMajor = kSparseOut || OP == OP_DSD || OP == OP_DSDT;   // items enumerate block rows
   extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A slabs, B slabs]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int pm = PAN == 2 ? wave >> 2 : 0;          // A panel / B panel of this wave
-  const int pn = PAN == 2 ? (wave >> 1) & 1 : 0;
-  const int arow0 = PAN == 2 ? 0 : (wave >> 1) * 32;  // first row of the wave inside its A panel
+  const int wq = wave / WB;                         // which 128x128 block of the tile: A panel pm, B panel pn
+  const int pm = wq / PB, pn = wq % PB;
+  const int arow0 = ((wave % WB) >> 1) * (32 * MI);  // first row of the wave inside its A panel
   const int hn = wave & 1;                          // which 64-column half of the B panel
   const int d = p.d, hb = p.hb, db = p.db;
   const size_t ldw = (size_t)p.E * p.h;             // leading dimension of W1 / dW1
-  const int ncu = (hb + PAN - 1) / PAN, nju = (db + PAN - 1) / PAN;   // column units / d units per row
+  // Which dimension the A panels and the B panels span: rows x block-columns (SDD, SDD^T), rows x d-blocks (DSD,
+  // DSD^T), block-columns x d-blocks (DS^TD), d-blocks x block-columns (DD^TS).
+  constexpr int UC = (kSparseOut || OP == OP_DDTS) ? PB : PA;   // block-columns per unit (where columns matter)
+  constexpr int UD = OP == OP_DDTS ? PA : PB;                   // d-blocks per unit
+  const int ncu = (hb + UC - 1) / UC, nju = (db + UD - 1) / UD;
 
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
@@ -112,7 +122,7 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
   int nk = 0;
   int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jd0 = 0;
   if constexpr (kRowMajor) {
-    if constexpr (PAN == 2) {
+    if constexpr (PA == 2) {
       if (major >= p.group_offsets[p.E]) return;
       const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
       r0 = rg >> 1;
@@ -126,29 +136,29 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
     first1 = p.row_offsets[r1];
     const int nblk = p.row_offsets[r0 + 1] - first0;
     if constexpr (kSparseOut) {
-      if (PAN * minor >= nblk) return;
-      b_ok[1] = PAN == 2 && 2 * minor + 1 < nblk;
-      first0 += PAN * minor;                        // block (r0, c0); (r0, c1) is the next one
-      first1 += PAN * minor;
+      if (PB * minor >= nblk) return;
+      b_ok[1] = PB == 2 && 2 * minor + 1 < nblk;
+      first0 += PB * minor;                         // block (r0, c0); (r0, c1) is the next one
+      first1 += PB * minor;
       c0 = p.column_indices[first0];
       c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
       nk = d / BK;
     } else {
-      jd0 = PAN * minor;
-      b_ok[1] = PAN == 2 && jd0 + 1 < db;
+      jd0 = PB * minor;
+      b_ok[1] = PB == 2 && jd0 + 1 < db;
       nk = kSub * nblk;
     }
   } else {
     // Both tile shapes are launched for the weight gradients; the routing decides on the device which one works.
     const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
-    if (want_small != (PAN == 1 ? 1 : 0)) return;
+    if (want_small != (PA * PB == 1 ? 1 : 0)) return;
     if (major >= p.E * ncu) return;
     const int e = p.expert_order[major / ncu];      // heaviest experts first
     const int cu = major % ncu;
-    jd0 = PAN * minor;
-    c0 = e * hb + PAN * cu;
-    const bool second_col = PAN == 2 && 2 * cu + 1 < hb;
-    const bool second_d = PAN == 2 && jd0 + 1 < db;
+    jd0 = UD * minor;
+    c0 = e * hb + UC * cu;
+    const bool second_col = UC == 2 && 2 * cu + 1 < hb;
+    const bool second_d = UD == 2 && jd0 + 1 < db;
     c1 = second_col ? c0 + 1 : c0;
     first0 = p.column_offsets_t[c0];
     first1 = p.column_offsets_t[c1];
@@ -211,13 +221,13 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
     }
   };
 
-  // Each wave moves 1 KB chunks `wave` and `wave + 8` of every slab.  All slabs are always loaded (a missing panel
+  // Each wave moves 1 KB chunk `wave` (and `wave + 8` when there are eight waves) of every slab.  All slabs are always loaded (a missing panel
   // re-reads its sibling): the number of loads per K tile must be a constant for the counted waits below.
   uint32_t oa[kCpw], ob[kCpw];
 #pragma unroll
   for (int i = 0; i < kCpw; ++i) {
-    oa[i] = dma_lane_offset<LA, BK>(wave + 8 * i, lane, lda);
-    ob[i] = dma_lane_offset<LB, BK>(wave + 8 * i, lane, ldb);
+    oa[i] = dma_lane_offset<LA, BK>(wave + NW * i, lane, lda);
+    ob[i] = dma_lane_offset<LB, BK>(wave + NW * i, lane, ldb);
   }
   // The loads are written as inline assembly on purpose: the compiler's own wait-count insertion treats a
   // direct-to-LDS load as aliasing every later LDS read and would wait for it before the first ds_read of the
@@ -232,11 +242,11 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
 #pragma unroll
     for (int i = 0; i < kCpw; ++i) {
       if (part == 0) {
-        dma16(a0 + oa[i], s + 8192 * i);
-        if (PAN == 2) dma16(a1 + oa[i], s + kPanelBytes + 8192 * i);
+        dma16(a0 + oa[i], s + NW * 1024 * i);
+        if (PA == 2) dma16(a1 + oa[i], s + kPanelBytes + NW * 1024 * i);
       } else {
-        dma16(b0 + ob[i], s + PAN * kPanelBytes + 8192 * i);
-        if (PAN == 2) dma16(b1 + ob[i], s + (PAN + 1) * kPanelBytes + 8192 * i);
+        dma16(b0 + ob[i], s + PA * kPanelBytes + NW * 1024 * i);
+        if (PB == 2) dma16(b1 + ob[i], s + (PA + 1) * kPanelBytes + NW * 1024 * i);
       }
     }
   };
@@ -269,7 +279,7 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
     const int next_stage = (kt + NS - 1) % NS;
     if (more) slab_ptrs(kt + NS - 1);
     const char* sa = lds + (kt % NS) * kStageBytes + pm * kPanelBytes;
-    const char* sb = lds + (kt % NS) * kStageBytes + (PAN + pn) * kPanelBytes;
+    const char* sb = lds + (kt % NS) * kStageBytes + (PA + pn) * kPanelBytes;
     // The loads of the next tile are spread over the first two K steps instead of being issued in one burst: a
     // wave cannot start its MFMAs before its own loads have been issued.
 #pragma unroll
@@ -368,20 +378,24 @@ __global__ void __launch_bounds__(kBsThreads, PAN == 2 ? 2 : 4) bsmm_kernel(cons
   }
 }
 
-template <int OP, int PAN, int NS>
+template <int OP, int PA, int PB, int NS, int NW>
 static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
   static bool configured = false;
-  constexpr int kLds = NS * 2 * PAN * 16384;
+  constexpr int kLds = NS * (PA + PB) * 16384;
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PAN, NS>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     configured = true;
   }
   const int items = ((majors + 3) / 4) * 4 * nminor;          // majors are consumed in runs of 4
   const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
-  hipLaunchKernelGGL((bsmm_kernel<OP, PAN, NS>), dim3(grid), dim3(kBsThreads), kLds, s, p);
+  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW>), dim3(grid), dim3(NW * 64), kLds, s, p);
 }
 
+// Other shapes the template covers were measured on MI355X and lost: 16 waves of 64x64 on the 256x256 tile (-2..6 %),
+// 256x128 tiles with three LDS stages (-15..20 %), K = 32 per stage with three to five stages (-5..8 %).  The products
+// are bound by operand delivery into LDS, not by load latency, so intensity wins over pipeline depth.
+//
 // Tile choice (host side, from the configuration only -- the routing is not known to the host):
 //  * 256x256 macro tiles, two LDS stages: when there are enough of them to fill 256 CUs a few times over; they halve
 //    the L2->LDS traffic per flop, which is what bounds the MFMA-bound configurations.
@@ -391,19 +405,19 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
 template <int OP>
 static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
   const int hb = p.hb, db = p.db;
-  const bool row_major = OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT;
-  const bool sparse_out = OP == OP_SDD || OP == OP_SDDT;
+  constexpr bool row_major = OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT;
+  constexpr bool sparse_out = OP == OP_SDD || OP == OP_SDDT;
   const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
   if (row_major) {
     bool small = (long long)a.groups_est * big_minor < 256 + (sparse_out ? 1 : 0);
     if (a.force_tile == 1) small = true;
     if (a.force_tile == 2) small = false;
-    if (small) launch_variant<OP, 1, 2>(p, a.r_max, sparse_out ? hb : db, s);
-    else       launch_variant<OP, 2, 2>(p, a.g_max, big_minor, s);
+    if (small) launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
+    else       launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
   } else {
     // the device-side flag sched[0] selects which of the two launches does the work (the other exits at once)
-    launch_variant<OP, 2, 2>(p, a.E * ((hb + 1) / 2), big_minor, s);
-    launch_variant<OP, 1, 2>(p, a.E * hb, db, s);
+    launch_variant<OP, 2, 2, 2, 8>(p, a.E * ((hb + 1) / 2), big_minor, s);
+    launch_variant<OP, 1, 1, 2, 8>(p, a.E * hb, db, s);
   }
 }
 
