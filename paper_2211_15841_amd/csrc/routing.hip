@@ -15,10 +15,9 @@ namespace dmoe {
 // The x tile is staged in LDS as fp32 and read as broadcasts, the Wr tile as fp32 rows.  Every (token, expert)
 // accumulator sees its products in ascending hidden index, one fused multiply-add each: a bf16 x bf16 product
 // is exact in fp32, so the sum is reproducible bit for bit by any implementation that keeps the order.
-constexpr int kRouterTPT = 4;
-constexpr int kRouterKT = 32;
+constexpr int kRouterKT = 64;
 
-template <int EPAD>
+template <int EPAD, int kRouterTPT>
 __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
                                                             const float* __restrict__ bias, float* __restrict__ logits,
                                                             int T, int d, int E) {
@@ -34,6 +33,7 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
   const int group = wave * GW + lane / EPAD;
   const int tile0 = blockIdx.x * TT;
   const int tok_local = group * kRouterTPT;
+  const bool vec_w = (E % 8) == 0;              // rows of Wr are 16-byte aligned
 
   for (int e0 = 0; e0 < E; e0 += EPAD) {
     float acc[kRouterTPT];
@@ -52,12 +52,25 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
         *reinterpret_cast<float4*>(&xs[tl * XP + c * 8]) = lo;
         *reinterpret_cast<float4*>(&xs[tl * XP + c * 8 + 4]) = hi;
       }
-      for (int q = tid; q < kRouterKT * EPAD; q += 256) {
-        const int i = q / EPAD, e = e0 + q % EPAD;
-        ws[q] = e < E ? bf16_to_f32(wr[(size_t)(i0 + i) * E + e]) : 0.0f;
+      if (vec_w && EPAD >= 8) {
+        for (int q = tid; q < kRouterKT * (EPAD / 8); q += 256) {
+          const int i = q / (EPAD / 8), c = q % (EPAD / 8);
+          const int e = e0 + c * 8;
+          uint4 raw = make_uint4(0, 0, 0, 0);
+          if (e < E) raw = *reinterpret_cast<const uint4*>(wr + (size_t)(i0 + i) * E + e);
+          float4 lo = make_float4(bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y));
+          float4 hi = make_float4(bf16_lo(raw.z), bf16_hi(raw.z), bf16_lo(raw.w), bf16_hi(raw.w));
+          *reinterpret_cast<float4*>(&ws[i * EPAD + c * 8]) = lo;
+          *reinterpret_cast<float4*>(&ws[i * EPAD + c * 8 + 4]) = hi;
+        }
+      } else {
+        for (int q = tid; q < kRouterKT * EPAD; q += 256) {
+          const int i = q / EPAD, e = e0 + q % EPAD;
+          ws[q] = e < E ? bf16_to_f32(wr[(size_t)(i0 + i) * E + e]) : 0.0f;
+        }
       }
       __syncthreads();
-#pragma unroll
+#pragma unroll 4
       for (int i = 0; i < kRouterKT; i += 4) {
         const float w0 = ws[(i + 0) * EPAD + el], w1 = ws[(i + 1) * EPAD + el];
         const float w2 = ws[(i + 2) * EPAD + el], w3 = ws[(i + 3) * EPAD + el];
@@ -207,16 +220,38 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
   __shared__ int n_s[kMaxExperts];
   __shared__ int scan_s[kMaxExperts];
   __shared__ int gscan_s[kMaxExperts];
+  __shared__ int part_s[kMaxExperts];
   const int tid = threadIdx.x;
-  int n = 0;
-  if (tid < E) {
-    for (int c = 0; c < nchunks; ++c) {
-      const int v = chunk_counts[(size_t)c * E + tid];
-      chunk_counts[(size_t)c * E + tid] = n;
-      n += v;
-    }
-    tokens_per_expert[tid] = n;
+  // L threads share one expert's column of chunk_counts: each sums a contiguous range of chunks, the ranges are
+  // scanned through LDS, then each thread rewrites its range as exclusive bases.
+  int epow = 1;
+  while (epow < E) epow <<= 1;
+  const int L = kMaxExperts / epow;
+  const int ex = tid % epow, part = tid / epow;
+  const int per = (nchunks + L - 1) / L;
+  const int cb = min(nchunks, part * per), ce = min(nchunks, cb + per);
+  int mine = 0;
+  if (ex < E)
+    for (int c = cb; c < ce; ++c) mine += chunk_counts[(size_t)c * E + ex];
+  part_s[tid] = mine;
+  __syncthreads();
+  int before = 0, n = 0;
+  for (int l = 0; l < L; ++l) {
+    const int v = part_s[l * epow + ex];
+    before += l < part ? v : 0;
+    n += v;
   }
+  if (ex < E) {
+    int run = before;
+    for (int c = cb; c < ce; ++c) {
+      const int v = chunk_counts[(size_t)c * E + ex];
+      chunk_counts[(size_t)c * E + ex] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  if (tid >= E) n = 0;                      // threads 0..E-1 (part 0, ex == tid) own expert tid from here on
+  if (tid < E) tokens_per_expert[tid] = n;
   const int padded = ((n + kBlock - 1) / kBlock) * kBlock;
   n_s[tid] = n;
   scan_s[tid] = tid < E ? padded : 0;
@@ -344,11 +379,17 @@ void launch_router(const dmoe_config& c, const bf16_t* x, const bf16_t* wr, cons
                    const dmoe_topology_t& t, hipStream_t s) {
   const int T = c.num_tokens, d = c.d_model, E = c.num_experts;
   const int epad = pow2_at_least(E < 4 ? 4 : E, 64);
+  // eight tokens per lane amortise the staging of Wr best, four give twice as many workgroups: use eight only when
+  // that still leaves at least two workgroups per CU
 #define DMOE_ROUTER_CASE(EP)                                                                                   \
   case EP: {                                                                                                   \
-    constexpr int TT = 4 * (64 / EP) * kRouterTPT;                                                             \
-    hipLaunchKernelGGL(router_logits_kernel<EP>, dim3((T + TT - 1) / TT), dim3(256), 0, s, x, wr, bias,        \
-                       t.logits, T, d, E);                                                                     \
+    constexpr int TT8 = 4 * (64 / EP) * 8, TT4 = 4 * (64 / EP) * 4;                                            \
+    if ((T + TT8 - 1) / TT8 >= 512)                                                                            \
+      hipLaunchKernelGGL((router_logits_kernel<EP, 8>), dim3((T + TT8 - 1) / TT8), dim3(256), 0, s, x, wr,     \
+                         bias, t.logits, T, d, E);                                                             \
+    else                                                                                                       \
+      hipLaunchKernelGGL((router_logits_kernel<EP, 4>), dim3((T + TT4 - 1) / TT4), dim3(256), 0, s, x, wr,     \
+                         bias, t.logits, T, d, E);                                                             \
   } break;
   switch (epad) {
     DMOE_ROUTER_CASE(4)
