@@ -283,8 +283,15 @@ __global__ void __launch_bounds__(256) dwr_mfma_kernel(const bf16_t* __restrict_
           xv = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c16 * 8);
           const int e = eb + c16 * 8;
           const float* src = dlogits + (size_t)t * E + e;
+          if ((E & 7) == 0) {                     // rows of dscores are 32-byte aligned: two 16-byte loads
+            if (e < E) {
+              const float4 p0 = *reinterpret_cast<const float4*>(src), p1 = *reinterpret_cast<const float4*>(src + 4);
+              v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+            }
+          } else {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) if (e + u < E) v[u] = src[u];
+            for (int u = 0; u < 8; ++u) if (e + u < E) v[u] = src[u];
+          }
         }
         bf16x8_v hi, lo;
         split8(v, hi, lo);
