@@ -52,6 +52,7 @@ struct BsParams {
   const int32_t* sched;
   int d, h, E, hb, db;
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
+  int patch;               // tiles per XCD patch (see patch_item)
 };
 
 template <int OP> struct OpLayouts;
@@ -63,11 +64,11 @@ template <> struct OpLayouts<OP_DSDT> { static constexpr int A = KC, B = KC; };
 template <> struct OpLayouts<OP_DDTS> { static constexpr int A = NC, B = NC; };
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup w runs on XCD w % 8).  Work items are cut into
-// patches of 32 consecutive items that share operands; patch p goes to XCD p % 8, so the 32 items of a patch run
-// side by side on the 32 CUs behind one L2, and heavy patches spread evenly over the XCDs.
-__device__ __forceinline__ int patch_item(int wg) {
+// patches of P consecutive items that share operands; patch p goes to XCD p % 8, so the items of a patch run
+// side by side on the CUs behind one L2 (P = 32: one per CU).  P = 1 deals the items out one by one.
+__device__ __forceinline__ int patch_item(int wg, int P) {
   const int xcd = wg & 7, slot = wg >> 3;
-  return ((slot / kPatch) * 8 + xcd) * kPatch + slot % kPatch;
+  return ((slot / P) * 8 + xcd) * P + slot % P;
 }
 
 // PA, PB = number of 128-row A panels and 128-column B panels of the tile:
@@ -110,7 +111,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
-  const int item = patch_item(blockIdx.x);
+  const int item = patch_item(blockIdx.x, p.patch);
   int major, minor;
   {
     const int nminor = kSparseOut ? ncu : nju;
@@ -431,6 +432,10 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.counts = t.counts;  p.sched = t.sched;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
+  // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
+  // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
+  // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level.
+  p.patch = (op == OP_DSTD || op == OP_DDTS) ? 1 : kPatch;
   switch (op) {
     case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;
     case OP_SDDT: launch_one<OP_SDDT>(p, a, s); break;
