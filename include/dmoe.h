@@ -93,7 +93,7 @@ typedef struct {
 
 /* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,
  * nnz_max = (P_max/128)*(h/128).  topology: the arrays of dmoe_topology_t; saved: what forward keeps for
- * backward (permuted tokens, both sparse activations, permuted expert output); scratch: the larger of what
+ * backward (permuted tokens, the sparse activation and the activation's derivative, permuted expert output); scratch: the larger of what
  * the three calls need (contents are dead after each call returns... after its work completes).             */
 DMOE_API int dmoe_sizes(const dmoe_config *cfg, size_t *topology_bytes, size_t *saved_bytes, size_t *scratch_bytes,
                int32_t *P_max, int32_t *nnz_max);
@@ -133,11 +133,11 @@ DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out
 #define DMOE_STAGE_SORT          1   /* histogram, offsets, stable ranks              (dmoe_topology) */
 #define DMOE_STAGE_TOPOLOGY      2   /* blocked-CSR-COO arrays and transpose indices  (dmoe_topology) */
 #define DMOE_STAGE_GATHER        3   /* padded gather                                 (dmoe_forward)  */
-#define DMOE_STAGE_SDD           4   /* H = Xp W1, A = gelu(H)                        (dmoe_forward)  */
+#define DMOE_STAGE_SDD           4   /* H = Xp W1, A = gelu(H), G = gelu'(H)          (dmoe_forward)  */
 #define DMOE_STAGE_DSD           5   /* Yp = A W2                                     (dmoe_forward)  */
 #define DMOE_STAGE_SCATTER       6   /* weighted un-permute                           (dmoe_forward)  */
 #define DMOE_STAGE_BWD_GATHER    7   /* dYp = w dY permuted, dweights                 (dmoe_backward) */
-#define DMOE_STAGE_SDDT          8   /* dA = dYp W2^T, dH = dA gelu'(H)               (dmoe_backward) */
+#define DMOE_STAGE_SDDT          8   /* dA = dYp W2^T, dH = dA G                      (dmoe_backward) */
 #define DMOE_STAGE_DSTD          9   /* dW2 = A^T dYp                                 (dmoe_backward) */
 #define DMOE_STAGE_DSDT         10   /* dXp = dH W1^T                                 (dmoe_backward) */
 #define DMOE_STAGE_DDTS         11   /* dW1 = Xp^T dH                                 (dmoe_backward) */

@@ -295,7 +295,7 @@ int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, c
   a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max; a.r_max = m.r_max;
   a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
 
-  ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * gelu'(H)
+  ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * G with G = gelu'(H) kept by forward
   a.dense_a = dyp; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = hval; a.out0 = dh; a.out1 = nullptr;
   launch_bsmm(OP_SDDT, a, s);
   ev.end(DMOE_STAGE_SDDT);

@@ -1,8 +1,8 @@
 // Block-sparse matrix products of the two-layer expert FFN on bf16 MFMA with fp32 accumulation (Section 5.1):
 //
-//   SDD    H  = Xp  W1          sampled on the nonzero blocks, epilogue A = gelu(H)       (forward, layer 1)
+//   SDD    H  = Xp  W1          sampled on the nonzero blocks, epilogue A = gelu(H), G = gelu'(H)   (forward, layer 1)
 //   DSD    Yp = A   W2          sparse lhs iterated through blocked CSR                   (forward, layer 2)
-//   SDD^T  dA = dYp W2^T        sampled on the nonzero blocks, epilogue dH = dA gelu'(H)  (layer-2 data gradient)
+//   SDD^T  dA = dYp W2^T        sampled on the nonzero blocks, epilogue dH = dA * G       (layer-2 data gradient)
 //   DS^TD  dW2 = A^T dYp        sparse lhs iterated through the transpose indices         (layer-2 weight gradient)
 //   DSD^T  dXp = dH W1^T                                                                  (layer-1 data gradient)
 //   DD^TS  dW1 = Xp^T dH        sparse rhs iterated through the transpose indices         (layer-1 weight gradient)
@@ -335,7 +335,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
     }
   };
-  if constexpr (OP == OP_SDDT) {                              // global -> staging tile: H, for gelu'
+  if constexpr (OP == OP_SDDT) {                              // global -> staging tile: G = gelu'(H)
     const bf16_t* src = p.sparse_in + blk;
 #pragma unroll
     for (int it = 0; it < 4 * MI; ++it) {
@@ -344,26 +344,39 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
           *reinterpret_cast<const uint4*>(src + (size_t)row * ldo + chunk * 8);
     }
   }
+  // SDD writes two tensors from the same fp32 values: out1 <- A = gelu(H) = H Phi(H) for the second layer, and
+  // out0 <- G = gelu'(H) = Phi(H) + H phi(H), which is all the backward pass needs of H (one evaluation of Phi and
+  // phi serves both, and SDD^T then only multiplies).
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const float v0 = acc[i][jj][4 * q + 0], v1 = acc[i][jj][4 * q + 1];
-        const float v2 = acc[i][jj][4 * q + 2], v3 = acc[i][jj][4 * q + 3];
+        float v[4] = {acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1], acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]};
         uint2 ov;
         if constexpr (OP == OP_SDDT) {
-          const uint2 hv = *slot(i, jj, q);
-          ov.x = pack_bf16(v0 * gelu_bwd(bf16_lo(hv.x)), v1 * gelu_bwd(bf16_hi(hv.x)));
-          ov.y = pack_bf16(v2 * gelu_bwd(bf16_lo(hv.y)), v3 * gelu_bwd(bf16_hi(hv.y)));
+          const uint2 gv = *slot(i, jj, q);
+          ov.x = pack_bf16(v[0] * bf16_lo(gv.x), v[1] * bf16_hi(gv.x));
+          ov.y = pack_bf16(v[2] * bf16_lo(gv.y), v[3] * bf16_hi(gv.y));
+        } else if constexpr (OP == OP_SDD) {
+          float g[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            float c, d0;
+            normal_cdf_pdf(v[u], c, d0);
+            g[u] = fmaf(v[u], d0, c);
+            v[u] *= c;
+            acc[i][jj][4 * q + u] = v[u];          // keep A for the second pass through the staging tile
+          }
+          ov.x = pack_bf16(g[0], g[1]);  ov.y = pack_bf16(g[2], g[3]);
         } else {
-          ov.x = pack_bf16(v0, v1);  ov.y = pack_bf16(v2, v3);
+          ov.x = pack_bf16(v[0], v[1]);  ov.y = pack_bf16(v[2], v[3]);
         }
         *slot(i, jj, q) = ov;
       }
   flush(out);
-  if constexpr (OP == OP_SDD) {                               // second output: A = gelu(H), from the fp32 values
+  if constexpr (OP == OP_SDD) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -371,8 +384,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           uint2 av;
-          av.x = pack_bf16(gelu_fwd(acc[i][jj][4 * q + 0]), gelu_fwd(acc[i][jj][4 * q + 1]));
-          av.y = pack_bf16(gelu_fwd(acc[i][jj][4 * q + 2]), gelu_fwd(acc[i][jj][4 * q + 3]));
+          av.x = pack_bf16(acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1]);
+          av.y = pack_bf16(acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]);
           *slot(i, jj, q) = av;
         }
     flush(p.out1 + blk);

@@ -47,17 +47,6 @@ __device__ __forceinline__ void normal_cdf_pdf(float v, float& cdf, float& pdf) 
   cdf = v < 0.0f ? tail : 1.0f - tail;
   pdf = ex * 0.39894228040143268f;
 }
-__device__ __forceinline__ float gelu_fwd(float v) {
-  float c, p;
-  normal_cdf_pdf(v, c, p);
-  return v * c;
-}
-__device__ __forceinline__ float gelu_bwd(float v) {   // d/dv [v Phi(v)] = Phi(v) + v phi(v)
-  float c, p;
-  normal_cdf_pdf(v, c, p);
-  return fmaf(v, p, c);
-}
-
 struct StageEvents {            // optional per-stage timing events (see dmoe_set_stage_events)
   hipEvent_t* ev;
   hipStream_t stream;
@@ -93,8 +82,8 @@ struct BsArgs {
   int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
-  const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: H for gelu')
-  bf16_t* out0;            // SDD: H blocks; SDDT: dH blocks; others: dense output
+  const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))
+  bf16_t* out0;            // SDD: G = gelu'(H) blocks; SDDT: dH blocks; others: dense output
   bf16_t* out1;            // SDD: A = gelu(H) blocks
 };
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s);

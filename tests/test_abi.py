@@ -70,3 +70,11 @@ def test_bind_and_calls_validate_pointers_without_launching():
     rc = lib.dmoe_backward(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.byref(topo), fake, 8, fake, fake, fake,
                            fake, fake, fake, s["scratch_bytes"], None)
     assert rc == -2
+
+
+def test_tile_mode_is_validated():
+    dm.dmoe_set_tile_mode(1)
+    dm.dmoe_set_tile_mode(2)
+    dm.dmoe_set_tile_mode(0)
+    with pytest.raises(dm.DMoEError, match="tile mode"):
+        dm.dmoe_set_tile_mode(3)

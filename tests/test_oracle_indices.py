@@ -202,7 +202,7 @@ def test_topology_generic_equals_closed_form_and_invariants(rows, hb):
     assert np.array_equal(back["row_indices_t"], topo["column_indices"])
 
 
-def test_survey_table_of_benchmark_configs_padding():
+def test_tiny_benchmark_config_padding_and_block_count():
     """Each expert's padded row count is ceil(n_e/128)*128 on the tiny benchmark configuration."""
     cfg = CONFIGS[0]
     inp = make_inputs(cfg)
