@@ -196,6 +196,8 @@ def main():
     ap.add_argument("--also", default="small_zipf1.0,medium_zipf1.2_top2",
                     help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2),
+                    help="0: the library's own tile choice (default); 1 / 2: force 128x128 / 256x256 tiles (experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -219,6 +221,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.tile_mode:
+        import paper_2211_15841_amd as dm
+        dm.dmoe_set_tile_mode(args.tile_mode)
     hipev = HipEvents()
     cfg = pick(args.config)
     main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu)

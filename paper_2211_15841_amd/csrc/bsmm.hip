@@ -32,6 +32,7 @@ namespace dmoe {
 constexpr int kBlockElems = kBlock * kBlock;  // 16384 values per sparse block
 constexpr int kBsThreads = 512;
 constexpr int kPatch = 32;                    // macro tiles that should run together on one XCD (one per CU)
+constexpr int kPatchSlack = 5;                // tolerated XCD imbalance, in 64ths, when the patch size is chosen
 
 
 struct BsParams {
@@ -52,7 +53,7 @@ struct BsParams {
   const int32_t* sched;
   int d, h, E, hb, db;
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
-  int patch;               // tiles per XCD patch (see patch_item)
+  int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
 };
 
 template <int OP> struct OpLayouts;
@@ -71,19 +72,37 @@ __device__ __forceinline__ int patch_item(int wg, int P) {
   return ((slot / P) * 8 + xcd) * P + slot % P;
 }
 
+// Patch size for `items` equally expensive tiles: the assignment of patches to XCDs is static, so with few patches
+// some XCDs get a whole patch more than others.  Take the largest power of two up to 32 whose most loaded XCD
+// carries at most `slack`/64 more than the best of them.
+__device__ __forceinline__ int balanced_patch(int items, int slack) {
+  int load[6], best = 0x7fffffff;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const int P = 32 >> i;
+    load[i] = (((items + P - 1) / P + 7) / 8) * P;
+    best = load[i] < best ? load[i] : best;
+  }
+  int P = 1;
+#pragma unroll
+  for (int i = 5; i >= 0; --i)
+    if (64 * load[i] <= (64 + slack) * best) P = 32 >> i;
+  return P;
+}
+
 // PA, PB = number of 128-row A panels and 128-column B panels of the tile:
 //   2,2 -> the 256x256 macro tile (each of 8 waves 128x64; or 16 waves of 64x64), two LDS stages;
 //   2,1 -> 256x128 (each wave 64x64), three LDS stages;
 //   1,1 -> a single 128x128 block shared by eight waves (32x64 each), two or more workgroups per CU: half the
 //          arithmetic intensity but four times as many work items, for under-filled launches.
-template <int OP, int PA, int PB, int NS, int NW>
+template <int OP, int PA, int PB, int NS, int NW, int BK = 64>
 __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
-  constexpr int BK = 64;                            // K per pipeline stage
   constexpr int kSub = kBlock / BK;                 // K tiles per 128-wide sparse block
   constexpr int kPanelBytes = 256 * BK;             // one 128 x 64 bf16 slab, either way round
   constexpr int kStageBytes = (PA + PB) * kPanelBytes;
-  constexpr int kCpw = 16 / NW;                     // 1 KB DMA chunks per wave per slab (a slab has 16)
+  constexpr int kCpw = (BK / 4) / NW;               // 1 KB DMA chunks per wave per slab (a slab has BK / 4)
+  static_assert(kCpw >= 1, "a slab must have at least one chunk per wave");
   constexpr int kDmaPerTile = (PA + PB) * kCpw;     // DMA instructions per wave per K tile
   // 32-row MFMA tiles per wave (a wave is always 64 columns wide): 8 waves on 2x2 blocks -> 128x64 per wave,
   // 16 waves on 2x2 blocks -> 64x64 per wave (four waves per SIMD), 8 waves on one block -> 32x64 per wave.
@@ -111,10 +130,15 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
-  const int item = patch_item(blockIdx.x, p.patch);
   int major, minor;
   {
     const int nminor = kSparseOut ? ncu : nju;
+    int P = 1;
+    if constexpr (kRowMajor) {
+      const int majors = PA == 2 ? p.group_offsets[p.E] : p.counts[1];
+      P = p.patch > 0 ? p.patch : balanced_patch((majors + 3) / 4 * 4 * nminor, -p.patch);
+    }
+    const int item = patch_item(blockIdx.x, P);
     const int run = item / (4 * nminor), rem = item % (4 * nminor);
     major = run * 4 + (rem & 3);
     minor = rem >> 2;
@@ -178,6 +202,26 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   else if constexpr (OP == OP_DSTD) { lda = kBlock; ldb = d; }
   else                              { lda = d;      ldb = kBlock; }
 
+  // The K loop of the products that walk the topology needs one to three index values per sparse block.  They are
+  // kept lane-distributed in registers, 64 blocks at a time (lane i holds the values of block 64 c + i), and picked
+  // out with v_readlane: an index load inside the loop would put its latency between the barrier and the loads
+  // that the barrier releases, with every wave waiting.
+  int ix0 = 0, ix1 = 0, ix2 = 0;
+  auto refill = [&](int kb0) {
+    const int n = nk / kSub - kb0;                  // blocks left from kb0 on
+    if (lane < n) {
+      if constexpr (OP == OP_DSD || OP == OP_DSDT) {
+        ix0 = p.column_indices[first0 + kb0 + lane];
+      } else if constexpr (OP == OP_DSTD || OP == OP_DDTS) {
+        ix0 = p.block_offsets_t[first0 + kb0 + lane];
+        ix1 = p.block_offsets_t[first1 + kb0 + lane];
+        ix2 = p.row_indices_t[first0 + kb0 + lane];
+      }
+    }
+    // consume the values here, so that the wait for these loads is placed inside this rarely taken branch and not
+    // in front of the v_readlane of every iteration
+    asm volatile("" : "+v"(ix0), "+v"(ix1), "+v"(ix2));
+  };
   auto slab_ptrs = [&](int kt) {
     if constexpr (OP == OP_SDD) {
       a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * BK;
@@ -191,30 +235,34 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       b1 = p.dense_b + (size_t)c1 * kBlock * d + kt * BK;
     } else if constexpr (OP == OP_DSD) {
       const int kb = kt / kSub, half = kt % kSub;
-      const int col = p.column_indices[first0 + kb];
+      if ((kt & (64 * kSub - 1)) == 0) refill(kb);
+      const int col = __builtin_amdgcn_readlane(ix0, kb & 63);
       a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
       a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
       b0 = p.dense_b + ((size_t)col * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else if constexpr (OP == OP_DSDT) {
       const int kb = kt / kSub, half = kt % kSub;
-      const int col = p.column_indices[first0 + kb];
+      if ((kt & (64 * kSub - 1)) == 0) refill(kb);
+      const int col = __builtin_amdgcn_readlane(ix0, kb & 63);
       a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
       a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
       b0 = p.dense_b + (size_t)jd0 * kBlock * ldw + (size_t)col * kBlock + half * BK;
       b1 = b0 + (b_ok[1] ? (size_t)kBlock * ldw : 0);
     } else if constexpr (OP == OP_DSTD) {
       const int i = kt / kSub, half = kt % kSub;
-      const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
-      const int row = p.row_indices_t[first0 + i];
+      if ((kt & (64 * kSub - 1)) == 0) refill(i);
+      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
       a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
       a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
       b0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       b1 = b0 + (b_ok[1] ? kBlock : 0);
     } else {  // OP_DDTS
       const int i = kt / kSub, half = kt % kSub;
-      const int blk0 = p.block_offsets_t[first0 + i], blk1 = p.block_offsets_t[first1 + i];
-      const int row = p.row_indices_t[first0 + i];
+      if ((kt & (64 * kSub - 1)) == 0) refill(i);
+      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
       a0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       a1 = a0 + (a_ok[1] ? kBlock : 0);
       b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
@@ -392,23 +440,26 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   }
 }
 
-template <int OP, int PA, int PB, int NS, int NW>
+template <int OP, int PA, int PB, int NS, int NW, int BK = 64>
 static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
   static bool configured = false;
-  constexpr int kLds = NS * (PA + PB) * 16384;
+  constexpr int kLds = NS * (PA + PB) * 256 * BK;
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW, BK>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     configured = true;
   }
   const int items = ((majors + 3) / 4) * 4 * nminor;          // majors are consumed in runs of 4
   const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
-  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW>), dim3(grid), dim3(NW * 64), kLds, s, p);
+  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK>), dim3(grid), dim3(NW * 64), kLds, s, p);
 }
 
 // Other shapes the template covers were measured on MI355X and lost: 16 waves of 64x64 on the 256x256 tile (-2..6 %),
-// 256x128 tiles with three LDS stages (-15..20 %), K = 32 per stage with three to five stages (-5..8 %).  The products
-// are bound by operand delivery into LDS, not by load latency, so intensity wins over pipeline depth.
+// 256x128 tiles with three LDS stages (-15..20 %), K = 32 per stage with three to five stages (-5..8 %; -20 % on the
+// 128x128 tile, where 64-byte row pieces double the number of memory requests), deeper pipelines on the 128x128 tile
+// at one workgroup per CU (no faster per K tile, and one workgroup per CU quantises worse), and four extra waves
+// that only issue the loads (-15 %).  The products are bound by operand delivery into LDS, not by load latency, so
+// intensity wins over pipeline depth.
 //
 // Tile choice (host side, from the configuration only -- the routing is not known to the host):
 //  * 256x256 macro tiles, two LDS stages: when there are enough of them to fill 256 CUs a few times over; they halve
@@ -448,7 +499,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level.
-  p.patch = (op == OP_DSTD || op == OP_DDTS) ? 1 : kPatch;
+  p.patch = (op == OP_DSTD || op == OP_DDTS) ? 1 : -kPatchSlack;
   switch (op) {
     case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;
     case OP_SDDT: launch_one<OP_SDDT>(p, a, s); break;
