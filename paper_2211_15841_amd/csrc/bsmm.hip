@@ -457,8 +457,10 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
 // Other shapes the template covers were measured on MI355X and lost: 16 waves of 64x64 on the 256x256 tile (-2..6 %),
 // 256x128 tiles with three LDS stages (-15..20 %), K = 32 per stage with three to five stages (-5..8 %; -20 % on the
 // 128x128 tile, where 64-byte row pieces double the number of memory requests), deeper pipelines on the 128x128 tile
-// at one workgroup per CU (no faster per K tile, and one workgroup per CU quantises worse), and four extra waves
-// that only issue the loads (-15 %).  The products are bound by operand delivery into LDS, not by load latency, so
+// at one workgroup per CU (no faster per K tile, and one workgroup per CU quantises worse), four extra waves that
+// only issue the loads (-15 %), and staging through registers (global_load + ds_write, -8..12 %).  A wave can issue
+// one direct-to-LDS load per ~120 cycles (a CU one per ~20, i.e. ~50 B/clk), which is why the loads are spread over
+// the first two K steps of the MFMA loop.  The products are bound by operand delivery into LDS, not by load latency, so
 // intensity wins over pipeline depth.
 //
 // Tile choice (host side, from the configuration only -- the routing is not known to the host):
