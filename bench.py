@@ -28,9 +28,18 @@ MATMUL_STAGES = ["sdd", "dsd", "sddt", "dstd", "dsdt", "ddts"]
 # Configurations whose block-sparse products are bound by HBM (weights are read once per ~128 rows: about
 # 128 flop/byte, below the 312 flop/byte ridge); the others are bound by the MFMA pipes.
 HBM_BOUND = {"tiny", "xs"}
-# HBM traffic per launch (bytes) of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled
-# by a copy kernel of known size; filled in from the summaries under profiles/ when they exist.
-MEASURED_TRAFFIC = {}
+# HBM traffic per launch (bytes) of each block-sparse product, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
+# being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
+MEASURED_TRAFFIC = {
+    ("xs", "sdd"): 279880362, ("xs", "dsd"): 217555537, ("xs", "sddt"): 279809731,
+    ("xs", "dstd"): 284008288, ("xs", "dsdt"): 217535673, ("xs", "ddts"): 283999687,
+    ("small_zipf1.0", "sdd"): 638468714, ("small_zipf1.0", "dsd"): 543527433, ("small_zipf1.0", "sddt"): 638206740,
+    ("small_zipf1.0", "dstd"): 980806486, ("small_zipf1.0", "dsdt"): 542793060, ("small_zipf1.0", "ddts"): 980813448,
+    ("medium_zipf1.2_top2", "sdd"): 2357545551, ("medium_zipf1.2_top2", "dsd"): 2569413875,
+    ("medium_zipf1.2_top2", "sddt"): 2365085181, ("medium_zipf1.2_top2", "dstd"): 2819992397,
+    ("medium_zipf1.2_top2", "dsdt"): 2616843218, ("medium_zipf1.2_top2", "ddts"): 2836204316,
+}
 
 
 class HipEvents:
