@@ -217,41 +217,56 @@ __global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], al[i], acc[i][j], 0, 0, 0);
       }
   }
-  // operands were swapped: lane l, register 4q+u of tile (i, j) is C[t0 + 32i + l%32][i0 + 32j + 8q + 4(l/32) + u]
+  // operands were swapped: lane l, register 4q+u of tile (i, j) is C[t0 + 32i + l%32][i0 + 32j + 8q + 4(l/32) + u].
+  // Straight from there every load of a dXp row and every store of dx would touch 32 rows with 8 bytes each; the
+  // wave's 64x64 fp32 tile goes through a wave-private LDS tile instead, and rows are then handled 128 bytes at a
+  // time (8 lanes per row, 16 bytes per lane).
+  __shared__ __attribute__((aligned(16))) float stg[4][64 * 68];
+  float* st = stg[wave];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int t = t0 + 32 * i + (lane & 31);
-    if (t >= T) continue;
-    int rows[kMaxTopK];
-#pragma unroll
-    for (int s = 0; s < kMaxTopK; ++s) rows[s] = s < k ? row_of[(size_t)t * k + s] : 0;
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = i0 + 32 * j + 8 * q + 4 * (lane >> 5);
-        float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(&st[(32 * i + (lane & 31)) * 68 + 32 * j + 8 * q + 4 * (lane >> 5)]) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+  // (same wave writes and reads: no barrier needed, the compiler orders the LDS accesses of one wave)
 #pragma unroll
-        for (int s = 0; s < kMaxTopK; ++s) {
-          if (s < k) {
-            const uint2 g = *reinterpret_cast<const uint2*>(dxp + (size_t)rows[s] * d + n);
-            v0 += bf16_lo(g.x); v1 += bf16_hi(g.x); v2 += bf16_lo(g.y); v3 += bf16_hi(g.y);
-          }
-        }
-        uint2 o;
-        o.x = pack_bf16(v0, v1);  o.y = pack_bf16(v2, v3);
-        *reinterpret_cast<uint2*>(dx + (size_t)t * d + n) = o;
-      }
+  for (int it = 0; it < 8; ++it) {
+    const int r = 8 * it + (lane >> 3), c8 = (lane & 7) * 8;
+    const int t = t0 + r;
+    if (t >= T) continue;
+    const float4 v0 = *reinterpret_cast<const float4*>(&st[r * 68 + c8]);
+    const float4 v1 = *reinterpret_cast<const float4*>(&st[r * 68 + c8 + 4]);
+    float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    for (int s = 0; s < k; ++s) {
+      const int row = row_of[(size_t)t * k + s];
+      const uint4 g = *reinterpret_cast<const uint4*>(dxp + (size_t)row * d + i0 + c8);
+      v[0] += bf16_lo(g.x); v[1] += bf16_hi(g.x); v[2] += bf16_lo(g.y); v[3] += bf16_hi(g.y);
+      v[4] += bf16_lo(g.z); v[5] += bf16_hi(g.z); v[6] += bf16_lo(g.w); v[7] += bf16_hi(g.w);
+    }
+    uint4 o;
+    o.x = pack_bf16(v[0], v[1]);  o.y = pack_bf16(v[2], v[3]);
+    o.z = pack_bf16(v[4], v[5]);  o.w = pack_bf16(v[6], v[7]);
+    *reinterpret_cast<uint4*>(dx + (size_t)t * d + i0 + c8) = o;
   }
 }
 
 // dWr[i, e] = sum_t x[t, i] * dscores[t, e].  Both operands have the reduction index t as their slow index, so both
 // are staged as [t][.] slabs and read with transposing LDS loads.  One workgroup = 128 hidden indices x up to 128
-// experts x a chunk of 256 tokens, written as an fp32 partial; the partials are then summed over chunks in
-// ascending order (deterministic).  dscores are fed as a bf16 hi/lo pair.
-constexpr int kDwrTok = 256;
+// experts x a chunk of tokens, written as an fp32 partial; the partials are then summed over chunks in ascending
+// order (deterministic).  dscores are fed as a bf16 hi/lo pair.  The chunk is 256 tokens when that still gives
+// every CU a workgroup, else 128 or 64: the kernel is a chain of load -> LDS -> MFMA steps of 64 tokens, and with
+// few workgroups their latencies are all exposed.
+static int dwr_chunk_tokens(const dmoe_config& c) {
+  const int col_tiles = c.d_model / 128;
+  for (int tok = 256; tok > 64; tok >>= 1)
+    if (((c.num_tokens + tok - 1) / tok) * col_tiles >= 256) return tok;
+  return 64;
+}
 __global__ void __launch_bounds__(256) dwr_mfma_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dlogits,
-                                                       float* __restrict__ partials, int T, int d, int E) {
+                                                       float* __restrict__ partials, int T, int d, int E, int kDwrTok) {
   __shared__ __attribute__((aligned(16))) char xs[16384];
   __shared__ __attribute__((aligned(16))) char hs[16384];
   __shared__ __attribute__((aligned(16))) char ls[16384];
@@ -334,7 +349,15 @@ __global__ void __launch_bounds__(256) dwr_reduce_kernel(const float* __restrict
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= n) return;
   float s = 0.0f;
-  for (int c = 0; c < nchunks; ++c) s += partials[(size_t)c * n + idx];
+  int c = 0;
+  for (; c + 8 <= nchunks; c += 8) {               // eight loads in flight; the additions stay in ascending order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partials[(size_t)(c + u) * n + idx];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; c < nchunks; ++c) s += partials[(size_t)c * n + idx];
   dwr[idx] = s;
 }
 
@@ -357,7 +380,10 @@ void launch_bwd_gather(const dmoe_config& c, const dmoe_topology_t& t, const bf1
                      t.counts, dyp, dweights, c.d_model, c.top_k);
 }
 
-int router_bwd_num_partials(const dmoe_config& c) { return (c.num_tokens + kDwrTok - 1) / kDwrTok; }
+int router_bwd_num_partials(const dmoe_config& c) {
+  const int tok = dwr_chunk_tokens(c);
+  return (c.num_tokens + tok - 1) / tok;
+}
 
 void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* x, const bf16_t* wr,
                        const float* dweights, const bf16_t* dxp, float* dlogits, float* partials, int num_partials,
@@ -386,7 +412,8 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
   else
     hipLaunchKernelGGL(dx_mfma_kernel<false>, dim3((T + 127) / 128, d / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
                        wr, dx, T, d, E, k);
-  hipLaunchKernelGGL(dwr_mfma_kernel, dim3(num_partials, d / 128), dim3(256), 0, s, x, dlogits, partials, T, d, E);
+  hipLaunchKernelGGL(dwr_mfma_kernel, dim3(num_partials, d / 128), dim3(256), 0, s, x, dlogits, partials, T, d, E,
+                     dwr_chunk_tokens(c));
   hipLaunchKernelGGL(dwr_reduce_kernel, dim3((d * E + 255) / 256), dim3(256), 0, s, partials, num_partials, d * E,
                      dw_router);
 }
