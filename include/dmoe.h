@@ -88,7 +88,9 @@ typedef struct {
   int32_t *row_group;          /* [G_max]   2*(first block-row of the group) + (1 if the group has a second row) */
   int32_t *sched;              /* [4]       sched[0] = 1 if the weight-gradient products should use 128x128 tiles
                                             (one expert holds so many rows that its 256x256 tiles alone would
-                                            outlast a balanced schedule), else 0; rest reserved                  */
+                                            outlast a balanced schedule), else 0; sched[1] = tiles per XCD patch
+                                            for those products (16 when no expert is large against an XCD's
+                                            share of the rows, else 1); rest reserved                            */
 } dmoe_topology_t;
 
 /* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,

@@ -130,13 +130,14 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
-  int major, minor;
+  int major, minor, P;
   {
     const int nminor = kSparseOut ? ncu : nju;
-    int P = 1;
     if constexpr (kRowMajor) {
       const int majors = PA == 2 ? p.group_offsets[p.E] : p.counts[1];
       P = p.patch > 0 ? p.patch : balanced_patch((majors + 3) / 4 * 4 * nminor, -p.patch);
+    } else {
+      P = p.sched[1];                               // 1 or 16, chosen with the routing in hand (offsets_kernel)
     }
     const int item = patch_item(blockIdx.x, P);
     const int run = item / (4 * nminor), rem = item % (4 * nminor);
@@ -178,7 +179,11 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
     if (want_small != (PA * PB == 1 ? 1 : 0)) return;
     if (major >= p.E * ncu) return;
-    const int e = p.expert_order[major / ncu];      // heaviest experts first
+    // heaviest experts first; with patches, consecutive experts go to consecutive XCDs, so every second group of
+    // eight is taken in reverse (the XCD that got the heaviest of one group gets the lightest of the next)
+    int rank = major / ncu;
+    if (P > 1 && (rank & 8) && (rank | 7) < p.E) rank = (rank & ~7) | (7 - (rank & 7));
+    const int e = p.expert_order[rank];
     const int cu = major % ncu;
     jd0 = UD * minor;
     c0 = e * hb + UC * cu;
@@ -500,7 +505,8 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
-  // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level.
+  // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless
+  // the routing is even enough for patches (sched[1], decided on the device).
   p.patch = (op == OP_DSTD || op == OP_DDTS) ? 1 : -kPatchSlack;
   switch (op) {
     case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;

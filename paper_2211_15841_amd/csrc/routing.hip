@@ -281,8 +281,15 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
     for (int e = 0; e < E; ++e) max_rows = max(max_rows, (n_s[e] + kBlock - 1) / kBlock);
     const long long tiles = (long long)((hb + 1) / 2) * ((db + 1) / 2);
     const long long share = (long long)(P / kBlock) * tiles / 256;
-    sched[0] = (2LL * max_rows > 3 * share && tiles < 256) ? 1 : 0;
-    sched[1] = sched[2] = sched[3] = 0;
+    const bool heavy = 2LL * max_rows > 3 * share;
+    sched[0] = (heavy && tiles < 256) ? 1 : 0;
+    // Patch size for the weight-gradient tiles (tiles of one XCD patch share operand slabs in that XCD's L2).  The
+    // patch -> XCD assignment is static, so patches are only used when they cannot unbalance the XCDs: no expert is
+    // large against an XCD's share of the rows (a hot expert's patches all cost its row count, and nine of them over
+    // eight XCDs cost 20 % on the skewed 64-expert configuration).  Otherwise the tiles are dealt out one by one,
+    // heaviest expert first.
+    sched[1] = (!heavy && 16LL * max_rows <= P / kBlock) ? 16 : 1;
+    sched[2] = sched[3] = 0;
   }
   if (tid < E) {                                           // position of expert `tid` in descending-load order
     int pos = 0;
