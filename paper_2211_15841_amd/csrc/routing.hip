@@ -15,6 +15,12 @@ namespace dmoe {
 // The x tile is staged in LDS as fp32 and read as broadcasts, the Wr tile as fp32 rows.  Every (token, expert)
 // accumulator sees its products in ascending hidden index, one fused multiply-add each: a bf16 x bf16 product
 // is exact in fp32, so the sum is reproducible bit for bit by any implementation that keeps the order.
+// The multiply-adds run on the matrix pipes all the same: v_mfma_f32_4x4x1_16b_f32 is sixteen independent 4x4 outer
+// products with K = 1, so every output element receives exactly one product per instruction, c + a*b rounded once.
+// Block b = lanes 4b..4b+3 holds four consecutive experts (B operand: one expert per lane, as before) and four
+// tokens (A operand: lane l supplies token l%4 of its group); accumulator register r of a lane is the score of
+// token r of the group for the lane's expert.  Issued once per hidden index in ascending order this is the same
+// chain, at a quarter of the issue slots and half the LDS reads.
 constexpr int kRouterKT = 64;
 
 template <int EPAD, int kRouterTPT>
@@ -36,9 +42,10 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
   const bool vec_w = (E % 8) == 0;              // rows of Wr are 16-byte aligned
 
   for (int e0 = 0; e0 < E; e0 += EPAD) {
-    float acc[kRouterTPT];
+    static_assert(kRouterTPT % 4 == 0, "tokens per lane come in groups of four (one 4x4 block each)");
+    f32x4_v acc4[kRouterTPT / 4];
 #pragma unroll
-    for (int j = 0; j < kRouterTPT; ++j) acc[j] = 0.0f;
+    for (int g = 0; g < kRouterTPT / 4; ++g) acc4[g] = f32x4_v{0.0f, 0.0f, 0.0f, 0.0f};
 
     for (int i0 = 0; i0 < d; i0 += kRouterKT) {
       __syncthreads();
@@ -75,12 +82,12 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
         const float w0 = ws[(i + 0) * EPAD + el], w1 = ws[(i + 1) * EPAD + el];
         const float w2 = ws[(i + 2) * EPAD + el], w3 = ws[(i + 3) * EPAD + el];
 #pragma unroll
-        for (int j = 0; j < kRouterTPT; ++j) {
-          const float4 xv = *reinterpret_cast<const float4*>(&xs[(tok_local + j) * XP + i]);
-          acc[j] = fmaf(xv.x, w0, acc[j]);
-          acc[j] = fmaf(xv.y, w1, acc[j]);
-          acc[j] = fmaf(xv.z, w2, acc[j]);
-          acc[j] = fmaf(xv.w, w3, acc[j]);
+        for (int g = 0; g < kRouterTPT / 4; ++g) {
+          const float4 xv = *reinterpret_cast<const float4*>(&xs[(tok_local + 4 * g + (lane & 3)) * XP + i]);
+          acc4[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.x, w0, acc4[g], 0, 0, 0);
+          acc4[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.y, w1, acc4[g], 0, 0, 0);
+          acc4[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.z, w2, acc4[g], 0, 0, 0);
+          acc4[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.w, w3, acc4[g], 0, 0, 0);
         }
       }
     }
@@ -90,7 +97,8 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
 #pragma unroll
       for (int j = 0; j < kRouterTPT; ++j) {
         const int t = tile0 + tok_local + j;
-        if (t < T) logits[(size_t)t * E + e] = bias ? acc[j] + b : acc[j];
+        const float v = acc4[j / 4][j % 4];
+        if (t < T) logits[(size_t)t * E + e] = bias ? v + b : v;
       }
     }
   }
