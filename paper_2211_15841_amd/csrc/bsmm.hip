@@ -32,6 +32,7 @@ namespace dmoe {
 constexpr int kBlockElems = kBlock * kBlock;  // 16384 values per sparse block
 constexpr int kBsThreads = 512;
 constexpr int kPatch = 32;                    // macro tiles that should run together on one XCD (one per CU)
+constexpr int kMaxGradGrid = 4096;             // cap on the grid of a weight-gradient launch (multiple of 8 * kPatch)
 constexpr int kPatchSlack = 5;                // tolerated XCD imbalance, in 64ths, when the patch size is chosen
 
 
@@ -54,6 +55,7 @@ struct BsParams {
   int d, h, E, hb, db;
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
+  int items;               // work items of this launch (weight gradients: may exceed the grid)
 };
 
 template <int OP> struct OpLayouts;
@@ -127,6 +129,14 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   constexpr int UD = OP == OP_DDTS ? PA : PB;                   // d-blocks per unit
   const int ncu = (hb + UC - 1) / UC, nju = (db + UD - 1) / UD;
 
+  // One workgroup, one tile for the products whose rows are tokens.  The weight-gradient launches are capped at
+  // kMaxGradGrid workgroups, each taking the items wgi, wgi + gridDim, ... (heaviest first, so the strided lists
+  // cost about the same): the launch that the device-side choice leaves idle then costs a few microseconds instead
+  // of one dispatch per tile (40-50 us for the 30 000 small tiles of the larger configurations), and the working
+  // one saves the workgroup launches (3-5 % on the macro tiles).  Under skewed routing a workgroup that drew a tile
+  // of the hot expert still takes its share of light ones afterwards (+6 % on those two kernels, lost in the noise
+  // of the whole step).
+  auto tile = [&](const int wgi) {
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
@@ -139,7 +149,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     } else {
       P = p.sched[1];                               // 1 or 16, chosen with the routing in hand (offsets_kernel)
     }
-    const int item = patch_item(blockIdx.x, P);
+    const int item = patch_item(wgi, P);
     const int run = item / (4 * nminor), rem = item % (4 * nminor);
     major = run * 4 + (rem & 3);
     minor = rem >> 2;
@@ -175,9 +185,6 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       nk = kSub * nblk;
     }
   } else {
-    // Both tile shapes are launched for the weight gradients; the routing decides on the device which one works.
-    const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
-    if (want_small != (PA * PB == 1 ? 1 : 0)) return;
     if (major >= p.E * ncu) return;
     // heaviest experts first; with patches, consecutive experts go to consecutive XCDs, so every second group of
     // eight is taken in reverse (the XCD that got the heaviest of one group gets the lightest of the next)
@@ -443,6 +450,19 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
         }
     flush(p.out1 + blk);
   }
+  };   // tile
+
+  if constexpr (kRowMajor) {
+    tile(blockIdx.x);
+  } else {
+    // Both tile shapes are launched for the weight gradients; the routing decides on the device which one works.
+    const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
+    if (want_small != (PA * PB == 1 ? 1 : 0)) return;
+    for (int wgi = blockIdx.x; wgi < p.items; wgi += gridDim.x) {
+      tile(wgi);
+      __syncthreads();                               // the epilogue's staging tiles are the next item's stages
+    }
+  }
 }
 
 template <int OP, int PA, int PB, int NS, int NW, int BK = 64>
@@ -455,8 +475,12 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
     configured = true;
   }
   const int items = ((majors + 3) / 4) * 4 * nminor;          // majors are consumed in runs of 4
-  const int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
-  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK>), dim3(grid), dim3(NW * 64), kLds, s, p);
+  int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
+  BsParams q = p;
+  q.items = grid;
+  constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS;
+  if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
+  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK>), dim3(grid), dim3(NW * 64), kLds, s, q);
 }
 
 // Other shapes the template covers were measured on MI355X and lost: 16 waves of 64x64 on the 256x256 tile (-2..6 %),
