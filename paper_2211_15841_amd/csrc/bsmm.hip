@@ -132,10 +132,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // One workgroup, one tile for the products whose rows are tokens.  The weight-gradient launches are capped at
   // kMaxGradGrid workgroups, each taking the items wgi, wgi + gridDim, ... (heaviest first, so the strided lists
   // cost about the same): the launch that the device-side choice leaves idle then costs a few microseconds instead
-  // of one dispatch per tile (40-50 us for the 30 000 small tiles of the larger configurations), and the working
-  // one saves the workgroup launches (3-5 % on the macro tiles).  Under skewed routing a workgroup that drew a tile
-  // of the hot expert still takes its share of light ones afterwards (+6 % on those two kernels, lost in the noise
-  // of the whole step).
+  // of one dispatch per tile (40-50 us for the 30 000 small tiles of the larger configurations; the same loop on the
+  // token-row products changed nothing).  Under skewed routing a workgroup that drew a tile of the hot expert still
+  // takes its share of light ones afterwards (+6 % on those two kernels, lost in the noise of the whole step).
   auto tile = [&](const int wgi) {
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
