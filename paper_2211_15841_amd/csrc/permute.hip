@@ -164,8 +164,9 @@ __global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__
                                                       const float* __restrict__ dlogits, const bf16_t* __restrict__ wr,
                                                       bf16_t* __restrict__ dx, int T, int d, int E, int k) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t0 = blockIdx.x * 128 + (wave >> 1) * 64;
-  const int i0 = blockIdx.y * 128 + (wave & 1) * 64;
+  // column tiles of one token block are neighbours in launch order: together they read and write whole rows
+  const int t0 = blockIdx.y * 128 + (wave >> 1) * 64;
+  const int i0 = blockIdx.x * 128 + (wave & 1) * 64;
   f32x16_v acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -232,24 +233,47 @@ __global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__
         *reinterpret_cast<float4*>(&st[(32 * i + (lane & 31)) * 68 + 32 * j + 8 * q + 4 * (lane >> 5)]) =
             make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
   // (same wave writes and reads: no barrier needed, the compiler orders the LDS accesses of one wave)
+  // The gathers of the first two slots of all eight row groups are issued before any of them is used: a chain of
+  // row_of -> dXp row -> store per group would expose two memory latencies eight times over.
+  const int c8 = (lane & 7) * 8;
+  int rows[8][2];
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
-    const int r = 8 * it + (lane >> 3), c8 = (lane & 7) * 8;
+    const int t = min(t0 + 8 * it + (lane >> 3), T - 1);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) rows[it][s] = s < k ? row_of[(size_t)t * k + s] : 0;
+  }
+  uint4 g[8][2];
+#pragma unroll
+  for (int it = 0; it < 8; ++it)
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      g[it][s] = make_uint4(0, 0, 0, 0);
+      if (s < k) g[it][s] = *reinterpret_cast<const uint4*>(dxp + (size_t)rows[it][s] * d + i0 + c8);
+    }
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = 8 * it + (lane >> 3);
     const int t = t0 + r;
-    if (t >= T) continue;
     const float4 v0 = *reinterpret_cast<const float4*>(&st[r * 68 + c8]);
     const float4 v1 = *reinterpret_cast<const float4*>(&st[r * 68 + c8 + 4]);
     float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-    for (int s = 0; s < k; ++s) {
-      const int row = row_of[(size_t)t * k + s];
-      const uint4 g = *reinterpret_cast<const uint4*>(dxp + (size_t)row * d + i0 + c8);
-      v[0] += bf16_lo(g.x); v[1] += bf16_hi(g.x); v[2] += bf16_lo(g.y); v[3] += bf16_hi(g.y);
-      v[4] += bf16_lo(g.z); v[5] += bf16_hi(g.z); v[6] += bf16_lo(g.w); v[7] += bf16_hi(g.w);
+    auto add = [&](const uint4 q) {
+      v[0] += bf16_lo(q.x); v[1] += bf16_hi(q.x); v[2] += bf16_lo(q.y); v[3] += bf16_hi(q.y);
+      v[4] += bf16_lo(q.z); v[5] += bf16_hi(q.z); v[6] += bf16_lo(q.w); v[7] += bf16_hi(q.w);
+    };
+    add(g[it][0]);                                   // slot order, as the sum is defined (zeros when k < 2)
+    add(g[it][1]);
+    if (t < T) {
+      for (int s = 2; s < k; ++s) {
+        const int row = row_of[(size_t)t * k + s];
+        add(*reinterpret_cast<const uint4*>(dxp + (size_t)row * d + i0 + c8));
+      }
+      uint4 o;
+      o.x = pack_bf16(v[0], v[1]);  o.y = pack_bf16(v[2], v[3]);
+      o.z = pack_bf16(v[4], v[5]);  o.w = pack_bf16(v[6], v[7]);
+      *reinterpret_cast<uint4*>(dx + (size_t)t * d + i0 + c8) = o;
     }
-    uint4 o;
-    o.x = pack_bf16(v[0], v[1]);  o.y = pack_bf16(v[2], v[3]);
-    o.z = pack_bf16(v[4], v[5]);  o.w = pack_bf16(v[6], v[7]);
-    *reinterpret_cast<uint4*>(dx + (size_t)t * d + i0 + c8) = o;
   }
 }
 
@@ -407,10 +431,10 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
   }
 #undef DMOE_DL_CASE
   if (E % 8 == 0)
-    hipLaunchKernelGGL(dx_mfma_kernel<true>, dim3((T + 127) / 128, d / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
+    hipLaunchKernelGGL(dx_mfma_kernel<true>, dim3(d / 128, (T + 127) / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
                        wr, dx, T, d, E, k);
   else
-    hipLaunchKernelGGL(dx_mfma_kernel<false>, dim3((T + 127) / 128, d / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
+    hipLaunchKernelGGL(dx_mfma_kernel<false>, dim3(d / 128, (T + 127) / 128), dim3(256), 0, s, dxp, t.row_of, dlogits,
                        wr, dx, T, d, E, k);
   hipLaunchKernelGGL(dwr_mfma_kernel, dim3(num_partials, d / 128), dim3(256), 0, s, x, dlogits, partials, T, d, E,
                      dwr_chunk_tokens(c));
