@@ -32,13 +32,12 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "sdd"): 279880362, ("xs", "dsd"): 217555537, ("xs", "sddt"): 279809731,
-    ("xs", "dstd"): 284008288, ("xs", "dsdt"): 217535673, ("xs", "ddts"): 283999687,
-    ("small_zipf1.0", "sdd"): 638468714, ("small_zipf1.0", "dsd"): 543527433, ("small_zipf1.0", "sddt"): 638206740,
-    ("small_zipf1.0", "dstd"): 980806486, ("small_zipf1.0", "dsdt"): 542793060, ("small_zipf1.0", "ddts"): 980813448,
-    ("medium_zipf1.2_top2", "sdd"): 2357545551, ("medium_zipf1.2_top2", "dsd"): 2569413875,
-    ("medium_zipf1.2_top2", "sddt"): 2365085181, ("medium_zipf1.2_top2", "dstd"): 2819992397,
-    ("medium_zipf1.2_top2", "dsdt"): 2616843218, ("medium_zipf1.2_top2", "ddts"): 2836204316,
+    ("xs", "sdd"): 279892173, ("xs", "dsd"): 217564774, ("xs", "sddt"): 279845683,
+    ("xs", "dstd"): 196621107, ("xs", "dsdt"): 217561907, ("xs", "ddts"): 196636262,
+    ("small_zipf1.0", "sdd"): 638837965, ("small_zipf1.0", "dsd"): 542679859, ("small_zipf1.0", "sddt"): 638236058,
+    ("small_zipf1.0", "dstd"): 980830003, ("small_zipf1.0", "dsdt"): 542817485, ("small_zipf1.0", "ddts"): 981277491,
+    ("medium_zipf1.2_top2", "sdd"): 2360531149, ("medium_zipf1.2_top2", "dsd"): 2597010432, ("medium_zipf1.2_top2", "sddt"): 2363080090,
+    ("medium_zipf1.2_top2", "dstd"): 2839578419, ("medium_zipf1.2_top2", "dsdt"): 2618286285, ("medium_zipf1.2_top2", "ddts"): 2875448934,
 }
 
 
