@@ -152,6 +152,43 @@ DMOE_API int dmoe_set_stage_events(void *events);
  * Meant for tests and tuning.                                                                                  */
 DMOE_API int dmoe_set_tile_mode(int mode);
 
+/* ---- General block-sparse products (Sections 4.2, 5.1) ---------------------------------------------------------
+ * The six products of the layer are general primitives on a 128x128 block-sparse matrix S of block_rows x block_cols
+ * blocks with ANY mask; the dMoE topology is the block-diagonal instance.  These entry points expose them for a
+ * caller-supplied mask, without the fused dMoE epilogues, one 128x128 block per workgroup.  Values of S: block b of
+ * the row-wise order (ascending row, ascending column inside a row) is a contiguous row-major 128x128 bf16 tile at
+ * element offset b*16384.  M = 128*block_rows, N = 128*block_cols, D = `dense` (a positive multiple of 128); dense
+ * matrices are row-major bf16, accumulation is fp32.  All data pointers are DEVICE pointers, 256-byte aligned,
+ * caller-owned; nothing is allocated.
+ *
+ *   DMOE_OP_SDD   a = X [M,D]   b = W [D,N]   out = S    S = (X W)   sampled on the mask     (Figure 3A)
+ *   DMOE_OP_DSD   a = S         b = W [N,D]   out [M,D]  = S W                                (Figure 3B)
+ *   DMOE_OP_SDDT  a = X [M,D]   b = W [N,D]   out = S    S = (X W^T) sampled on the mask
+ *   DMOE_OP_DSTD  a = S         b = X [M,D]   out [N,D]  = S^T X      (through the transpose indices, Section 5.1.4)
+ *   DMOE_OP_DSDT  a = S         b = W [D,N]   out [M,D]  = S W^T
+ *   DMOE_OP_DDTS  a = X [M,D]   b = S         out [D,N]  = X^T S      (through the transpose indices)
+ */
+enum { DMOE_OP_SDD = 0, DMOE_OP_DSD = 1, DMOE_OP_SDDT = 2, DMOE_OP_DSTD = 3, DMOE_OP_DSDT = 4, DMOE_OP_DDTS = 5 };
+
+/* Bytes of device memory that the topology of a mask with `nnz` nonzero blocks needs (host pointer out).
+ * Errors: DMOE_EINVAL (dimensions < 1, 128*dimension >= 2^24, nnz out of range).                               */
+DMOE_API int dmoe_bsmm_sizes(int block_rows, int block_cols, int nnz, size_t *topology_bytes);
+
+/* Encode `mask` (HOST pointer, row-major [block_rows][block_cols] bytes, nonzero = block present) as row_offsets,
+ * column_indices, row_indices and the transpose indices (Sections 5.1.3-5.1.4) and copy them into `topology_mem`
+ * (device, `bytes` >= dmoe_bsmm_sizes).  Fills `out` (host struct; the arrays a mask does not have point at zeros) and
+ * `nnz_out` (host, may be NULL).  A set-up call: the encoding runs on the host and the copy is synchronous.
+ * Errors: DMOE_EINVAL, DMOE_ENOMEM (buffer too small), DMOE_ELAUNCH (copy failed).                              */
+DMOE_API int dmoe_bsmm_topology(const uint8_t *mask, int block_rows, int block_cols, void *topology_mem, size_t bytes,
+                                dmoe_topology_t *out, int32_t *nnz_out);
+
+/* Enqueue one product (table above) on `stream`; asynchronous.  `topo` must come from dmoe_bsmm_topology with the same
+ * block_rows and block_cols.  Rows of S without blocks give zero rows of the DSD / DSD^T output, columns without
+ * blocks zero rows of the DS^TD output and zero columns of the DD^TS output.
+ * Errors: DMOE_EINVAL (unknown op, NULL or misaligned pointer, dense not a multiple of 128), DMOE_ELAUNCH.       */
+DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int block_cols, int dense, const void *a,
+                       const void *b, void *out, void *stream);
+
 /* Message for the last error returned on this thread (host pointer to static thread-local storage). */
 DMOE_API const char *dmoe_last_error(void);
 

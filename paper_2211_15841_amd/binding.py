@@ -62,9 +62,15 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_topology_counts_host.argtypes = [POINTER(DMoETopology), POINTER(c_int32), c_void_p]
     lib.dmoe_set_stage_events.argtypes = [c_void_p]
     lib.dmoe_set_tile_mode.argtypes = [ctypes.c_int]
+    lib.dmoe_bsmm_sizes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(c_size_t)]
+    lib.dmoe_bsmm_topology.argtypes = [c_void_p, ctypes.c_int, ctypes.c_int, c_void_p, c_size_t,
+                                       POINTER(DMoETopology), POINTER(c_int32)]
+    lib.dmoe_bsmm.argtypes = [ctypes.c_int, POINTER(DMoETopology), ctypes.c_int, ctypes.c_int, ctypes.c_int, c_void_p,
+                              c_void_p, c_void_p, c_void_p]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
-                 "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode"):
+                 "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
+                 "dmoe_bsmm_topology", "dmoe_bsmm"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -128,6 +134,75 @@ def dmoe_topology_counts_host(topo, stream=None):
     out = (c_int32 * 4)()
     _check(load_library().dmoe_topology_counts_host(byref(topo), out, _stream(stream)))
     return list(out)
+
+
+OP_SDD, OP_DSD, OP_SDDT, OP_DSTD, OP_DSDT, OP_DDTS = range(6)
+
+
+def dmoe_bsmm_sizes(block_rows: int, block_cols: int, nnz: int) -> int:
+    nbytes = c_size_t()
+    _check(load_library().dmoe_bsmm_sizes(block_rows, block_cols, nnz, byref(nbytes)))
+    return nbytes.value
+
+
+def dmoe_bsmm_topology(mask, topology_mem, nbytes: int):
+    """mask: host uint8 array [block_rows, block_cols] (numpy, C-contiguous).  Returns (topology struct, nnz)."""
+    rows, cols = mask.shape
+    topo, nnz = DMoETopology(), c_int32()
+    _check(load_library().dmoe_bsmm_topology(mask.ctypes.data, rows, cols, _ptr(topology_mem), nbytes, byref(topo),
+                                             byref(nnz)))
+    return topo, nnz.value
+
+
+def dmoe_bsmm(op: int, topo, block_rows: int, block_cols: int, dense: int, a, b, out, stream=None):
+    _check(load_library().dmoe_bsmm(op, byref(topo), block_rows, block_cols, dense, _ptr(a), _ptr(b), _ptr(out),
+                                    _stream(stream)))
+
+
+class BlockSparse:
+    """A 128x128 block mask on the device plus the six products on it (argument marshalling only)."""
+
+    def __init__(self, mask, device="cuda:0"):
+        import numpy as np
+        self.mask = np.ascontiguousarray(mask, dtype=np.uint8)
+        self.rows, self.cols = self.mask.shape
+        nbytes = dmoe_bsmm_sizes(self.rows, self.cols, int((self.mask != 0).sum()))
+        self.topology_mem = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.topo, self.nnz = dmoe_bsmm_topology(self.mask, self.topology_mem, nbytes)
+        self.device = device
+
+    def _out(self, *shape):
+        return torch.empty(*shape, dtype=torch.bfloat16, device=self.device)
+
+    def sdd(self, x, w, stream=None):        # x [M, D], w [D, N] -> S [nnz, 128, 128]
+        out = self._out(max(self.nnz, 1), 128, 128)
+        dmoe_bsmm(OP_SDD, self.topo, self.rows, self.cols, x.shape[1], x, w, out, stream)
+        return out[:self.nnz]
+
+    def sddt(self, x, w, stream=None):       # x [M, D], w [N, D] -> S
+        out = self._out(max(self.nnz, 1), 128, 128)
+        dmoe_bsmm(OP_SDDT, self.topo, self.rows, self.cols, x.shape[1], x, w, out, stream)
+        return out[:self.nnz]
+
+    def dsd(self, s, w, stream=None):        # s [nnz, 128, 128], w [N, D] -> [M, D]
+        out = self._out(self.rows * 128, w.shape[1])
+        dmoe_bsmm(OP_DSD, self.topo, self.rows, self.cols, w.shape[1], s, w, out, stream)
+        return out
+
+    def dsdt(self, s, w, stream=None):       # w [D, N] -> [M, D]
+        out = self._out(self.rows * 128, w.shape[0])
+        dmoe_bsmm(OP_DSDT, self.topo, self.rows, self.cols, w.shape[0], s, w, out, stream)
+        return out
+
+    def dstd(self, s, x, stream=None):       # x [M, D] -> [N, D]
+        out = self._out(self.cols * 128, x.shape[1])
+        dmoe_bsmm(OP_DSTD, self.topo, self.rows, self.cols, x.shape[1], s, x, out, stream)
+        return out
+
+    def ddts(self, x, s, stream=None):       # x [M, D] -> [D, N]
+        out = self._out(x.shape[1], self.cols * 128)
+        dmoe_bsmm(OP_DDTS, self.topo, self.rows, self.cols, x.shape[1], x, s, out, stream)
+        return out
 
 
 def dmoe_set_tile_mode(mode: int):

@@ -11,7 +11,7 @@ static thread_local char g_err[512] = "";
 static thread_local hipEvent_t* g_events = nullptr;
 static int g_force_tile = 0;
 
-static int fail(int code, const char* fmt, ...) {
+int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
@@ -112,7 +112,7 @@ static ScratchLayout scratch_layout(const Dims& m) {
   return l;
 }
 
-static int check_ptr(const void* p, const char* name) {
+int check_ptr(const void* p, const char* name) {
   if (!p) return fail(DMOE_EINVAL, "%s is NULL", name);
   if (!aligned(p)) return fail(DMOE_EINVAL, "%s is not 256-byte aligned", name);
   return DMOE_OK;
@@ -127,7 +127,7 @@ static int check_topo(const dmoe_topology_t* t) {
     if (!ps[i]) return fail(DMOE_EINVAL, "topology array %d is NULL (call dmoe_topology_bind first)", i);
   return DMOE_OK;
 }
-static int launch_status() {
+int launch_status() {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(DMOE_ELAUNCH, "HIP error while enqueueing: %s", hipGetErrorString(e));
   return DMOE_OK;

@@ -56,6 +56,7 @@ struct BsParams {
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
   int items;               // work items of this launch (weight gradients: may exceed the grid)
+  int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
 };
 
 template <int OP> struct OpLayouts;
@@ -394,7 +395,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
     }
   };
-  if constexpr (OP == OP_SDDT) {                              // global -> staging tile: G = gelu'(H)
+  if (OP == OP_SDDT && !p.plain) {                            // global -> staging tile: G = gelu'(H)
     const bf16_t* src = p.sparse_in + blk;
 #pragma unroll
     for (int it = 0; it < 4 * MI; ++it) {
@@ -414,11 +415,11 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       for (int q = 0; q < 4; ++q) {
         float v[4] = {acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1], acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]};
         uint2 ov;
-        if constexpr (OP == OP_SDDT) {
+        if (OP == OP_SDDT && !p.plain) {
           const uint2 gv = *slot(i, jj, q);
           ov.x = pack_bf16(v[0] * bf16_lo(gv.x), v[1] * bf16_hi(gv.x));
           ov.y = pack_bf16(v[2] * bf16_lo(gv.y), v[3] * bf16_hi(gv.y));
-        } else if constexpr (OP == OP_SDD) {
+        } else if (OP == OP_SDD && !p.plain) {
           float g[4];
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
@@ -435,7 +436,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
         *slot(i, jj, q) = ov;
       }
   flush(out);
-  if constexpr (OP == OP_SDD) {
+  if (OP == OP_SDD && !p.plain) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -526,6 +527,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.counts = t.counts;  p.sched = t.sched;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
+  p.plain = a.plain;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless

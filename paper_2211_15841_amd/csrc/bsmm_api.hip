@@ -1,0 +1,147 @@
+// C ABI of the general block-sparse products (declared in include/dmoe.h): the same six kernels that the dMoE layer
+// uses, on a caller-supplied 128x128 block mask of any shape (Sections 4.2 and 5.1: the products are general
+// primitives; the block-diagonal dMoE topology is one instance).  The topology of a mask is encoded on the host
+// (hybrid blocked-CSR-COO plus transpose indices, Sections 5.1.3-5.1.4) and uploaded; this is a set-up call, not
+// part of any hot path.  The products run one 128x128 block per workgroup and without the fused dMoE epilogues.
+#include "common.h"
+#include <vector>
+
+namespace dmoe {
+
+struct MaskLayout { size_t off[8]; size_t total; };
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+static MaskLayout mask_layout(int R, int C, int nnz) {
+  const size_t n[8] = {
+      (size_t)(R + 1) * 4,   // row_offsets
+      (size_t)nnz * 4,       // column_indices
+      (size_t)nnz * 4,       // row_indices
+      (size_t)(C + 1) * 4,   // column_offsets_t
+      (size_t)nnz * 4,       // row_indices_t
+      (size_t)nnz * 4,       // block_offsets_t
+      64,                    // counts[4] | sched[4] | expert_order[1] | group_offsets[2] | zero
+      256,                   // zeros: the arrays of dmoe_topology_t that a mask does not have
+  };
+  MaskLayout l;
+  size_t at = 0;
+  for (int i = 0; i < 8; ++i) { l.off[i] = at; at += align256(n[i] ? n[i] : 4); }
+  l.total = at;
+  return l;
+}
+
+static int check_mask_dims(int R, int C, int nnz) {
+  if (R < 1 || C < 1) return fail(DMOE_EINVAL, "block_rows and block_cols must be >= 1 (got %d, %d)", R, C);
+  if ((long long)R * kBlock >= (1ll << 24) || (long long)C * kBlock >= (1ll << 24))
+    return fail(DMOE_EINVAL, "matrix dimensions must stay below 2^24");
+  if (nnz < 0 || (long long)nnz > (long long)R * C || nnz >= (1 << 27))
+    return fail(DMOE_EINVAL, "nnz out of range (got %d)", nnz);
+  return DMOE_OK;
+}
+
+}  // namespace dmoe
+
+using namespace dmoe;
+
+extern "C" {
+
+int dmoe_bsmm_sizes(int block_rows, int block_cols, int nnz, size_t* topology_bytes) {
+  if (int rc = check_mask_dims(block_rows, block_cols, nnz)) return rc;
+  if (topology_bytes) *topology_bytes = mask_layout(block_rows, block_cols, nnz).total;
+  return DMOE_OK;
+}
+
+int dmoe_bsmm_topology(const uint8_t* mask, int block_rows, int block_cols, void* topology_mem, size_t bytes,
+                       dmoe_topology_t* out, int32_t* nnz_out) {
+  const int R = block_rows, C = block_cols;
+  if (!mask) return fail(DMOE_EINVAL, "mask is NULL");
+  if (!out) return fail(DMOE_EINVAL, "out is NULL");
+  if (int rc = check_mask_dims(R, C, 0)) return rc;
+  if (int rc = check_ptr(topology_mem, "topology_mem")) return rc;
+  long long count = 0;
+  for (long long i = 0; i < (long long)R * C; ++i) count += mask[i] != 0;
+  if (int rc = check_mask_dims(R, C, (int)count)) return rc;
+  const int nnz = (int)count;
+  const MaskLayout l = mask_layout(R, C, nnz);
+  if (bytes < l.total) return fail(DMOE_ENOMEM, "topology buffer has %zu bytes, needs %zu", bytes, l.total);
+
+  // primary encoding: blocks numbered row by row, ascending column inside a row
+  std::vector<char> host(l.total, 0);
+  int32_t* row_offsets = reinterpret_cast<int32_t*>(host.data() + l.off[0]);
+  int32_t* column_indices = reinterpret_cast<int32_t*>(host.data() + l.off[1]);
+  int32_t* row_indices = reinterpret_cast<int32_t*>(host.data() + l.off[2]);
+  int32_t* column_offsets_t = reinterpret_cast<int32_t*>(host.data() + l.off[3]);
+  int32_t* row_indices_t = reinterpret_cast<int32_t*>(host.data() + l.off[4]);
+  int32_t* block_offsets_t = reinterpret_cast<int32_t*>(host.data() + l.off[5]);
+  int32_t* small = reinterpret_cast<int32_t*>(host.data() + l.off[6]);
+  int b = 0;
+  for (int r = 0; r < R; ++r) {
+    row_offsets[r] = b;
+    for (int c = 0; c < C; ++c)
+      if (mask[(size_t)r * C + c]) { column_indices[b] = c; row_indices[b] = r; ++b; }
+  }
+  row_offsets[R] = b;
+  // transpose indices: the blocks of each column in ascending row order, each with its offset in the primary order
+  std::vector<int32_t> fill(C + 1, 0);
+  for (int i = 0; i < nnz; ++i) ++fill[column_indices[i] + 1];
+  for (int c = 0; c < C; ++c) fill[c + 1] += fill[c];
+  for (int c = 0; c <= C; ++c) column_offsets_t[c] = fill[c];
+  for (int i = 0; i < nnz; ++i) {                    // primary order is ascending in the row index already
+    const int at = fill[column_indices[i]]++;
+    row_indices_t[at] = row_indices[i];
+    block_offsets_t[at] = i;
+  }
+  small[0] = R * kBlock;  small[1] = R;  small[2] = nnz;  small[3] = 0;      // counts
+  small[4] = 1;  small[5] = 1;  small[6] = 0;  small[7] = 0;                  // sched: one block per workgroup, no patches
+  small[8] = 0;                                                               // expert_order[0]
+  small[9] = 0;  small[10] = 0;                                               // group_offsets (no row groups)
+
+  if (hipMemcpy(topology_mem, host.data(), l.total, hipMemcpyHostToDevice) != hipSuccess)
+    return fail(DMOE_ELAUNCH, "copying the topology to the device failed: %s", hipGetErrorString(hipGetLastError()));
+
+  char* d = static_cast<char*>(topology_mem);
+  int32_t* zi = reinterpret_cast<int32_t*>(d + l.off[7]);
+  int32_t* sm = reinterpret_cast<int32_t*>(d + l.off[6]);
+  out->expert_idx = zi;  out->weights = reinterpret_cast<float*>(zi);  out->logits = reinterpret_cast<float*>(zi);
+  out->tokens_per_expert = zi;  out->padded_offsets = zi;  out->row_of = zi;  out->token_of = zi;
+  out->row_offsets = reinterpret_cast<int32_t*>(d + l.off[0]);
+  out->column_indices = reinterpret_cast<int32_t*>(d + l.off[1]);
+  out->row_indices = reinterpret_cast<int32_t*>(d + l.off[2]);
+  out->column_offsets_t = reinterpret_cast<int32_t*>(d + l.off[3]);
+  out->row_indices_t = reinterpret_cast<int32_t*>(d + l.off[4]);
+  out->block_offsets_t = reinterpret_cast<int32_t*>(d + l.off[5]);
+  out->counts = sm;  out->sched = sm + 4;  out->expert_order = sm + 8;  out->group_offsets = sm + 9;
+  out->row_group = zi;
+  if (nnz_out) *nnz_out = nnz;
+  return DMOE_OK;
+}
+
+int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_cols, int dense, const void* a,
+              const void* b, void* out, void* stream) {
+  if (op < DMOE_OP_SDD || op > DMOE_OP_DDTS) return fail(DMOE_EINVAL, "unknown product %d", op);
+  if (!topo || !topo->row_offsets || !topo->counts) return fail(DMOE_EINVAL, "topology is NULL or not built");
+  if (int rc = check_mask_dims(block_rows, block_cols, 0)) return rc;
+  if (dense < kBlock || dense % kBlock) return fail(DMOE_EINVAL, "dense must be a positive multiple of 128 (got %d)", dense);
+  if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32))
+    return fail(DMOE_EINVAL, "operands too large");
+  if (int rc = check_ptr(a, "a")) return rc;
+  if (int rc = check_ptr(b, "b")) return rc;
+  if (int rc = check_ptr(out, "out")) return rc;
+  BsArgs g{};
+  g.topo = topo;  g.d = dense;  g.h = block_cols * kBlock;  g.E = 1;
+  g.r_max = block_rows;  g.g_max = 0;  g.groups_est = 0;  g.force_tile = 1;  g.plain = 1;
+  const bf16_t* pa = static_cast<const bf16_t*>(a);
+  const bf16_t* pb = static_cast<const bf16_t*>(b);
+  g.out0 = static_cast<bf16_t*>(out);
+  switch (op) {
+    case DMOE_OP_SDD:  g.dense_a = pa;  g.dense_b = pb;  break;      // S = X W
+    case DMOE_OP_DSD:  g.sparse_in = pa;  g.dense_b = pb;  break;    // Y = S W
+    case DMOE_OP_SDDT: g.dense_a = pa;  g.dense_b = pb;  break;      // S = X W^T
+    case DMOE_OP_DSTD: g.sparse_in = pa;  g.dense_a = pb;  break;    // Y = S^T X
+    case DMOE_OP_DSDT: g.sparse_in = pa;  g.dense_b = pb;  break;    // Y = S W^T
+    case DMOE_OP_DDTS: g.dense_a = pa;  g.sparse_in = pb;  break;    // Y = X^T S
+  }
+  (void)hipGetLastError();
+  launch_bsmm(static_cast<BsOp>(op), g, static_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+}  // extern "C"

@@ -80,6 +80,7 @@ struct BsArgs {
   int g_max, r_max;        // upper bounds on the number of row groups / block rows
   int groups_est;          // T*k/256: row groups if the routing were perfectly packed (tile-size heuristic)
   int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
+  int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))
@@ -87,5 +88,10 @@ struct BsArgs {
   bf16_t* out1;            // SDD: A = gelu(H) blocks
 };
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s);
+
+// ---- host-side helpers shared by the C-ABI source files ----------------------------------------------------------
+int fail(int code, const char* fmt, ...);           // records the message for dmoe_last_error, returns `code`
+int check_ptr(const void* p, const char* name);     // non-NULL and 256-byte aligned
+int launch_status();                                // DMOE_OK, or DMOE_ELAUNCH with the pending HIP error
 
 }  // namespace dmoe

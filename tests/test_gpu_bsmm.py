@@ -1,0 +1,102 @@
+"""Parity of the general block-sparse products (dmoe_bsmm) with their CPU oracle on arbitrary block masks:
+element by element, same seeded bf16 inputs, through the C-ABI.  Tolerance as for the layer: the outputs are
+rounded to bf16 once (2^-9 relative) after an fp32 accumulation, so max|G - O| <= 1e-2 * max|O| with room to spare."""
+import zlib
+
+import numpy as np
+import pytest
+
+from dmoe_inputs import f32_to_bf16_bits, bf16_bits_to_f32
+from oracle import bsmm_oracle as bo
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16(rng, shape, scale=1.0):
+    bits = f32_to_bf16_bits((scale * rng.standard_normal(shape)).astype(np.float32))
+    return bits, bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def _dev(bits):
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def _host(t):
+    return bf16_bits_to_f32(t.view(__import__("torch").int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+
+
+def _close(got, want, what):
+    scale = max(float(np.abs(want).max()), 1e-30)
+    err = float(np.abs(got - want).max()) / scale
+    assert err <= 1e-2, "%s: max relative error %.3e" % (what, err)
+
+
+MASKS = {
+    "random_40pct": lambda rng: (rng.random((7, 9)) < 0.4).astype(np.uint8),
+    "dense": lambda rng: np.ones((3, 4), dtype=np.uint8),
+    "diagonal": lambda rng: np.eye(5, dtype=np.uint8),
+    "empty_rows_and_columns": lambda rng: np.array([[0, 1, 0, 1], [0, 0, 0, 0], [1, 1, 0, 0]], dtype=np.uint8),
+    "single_block": lambda rng: np.array([[1]], dtype=np.uint8),
+    "tall_column": lambda rng: np.ones((70, 1), dtype=np.uint8),     # a column of more than 64 blocks
+    "wide_row": lambda rng: np.ones((1, 70), dtype=np.uint8),        # a row of more than 64 blocks
+    "banded": lambda rng: np.triu(np.tril(np.ones((12, 12), dtype=np.uint8), 1), -1),
+}
+
+
+@pytest.mark.parametrize("name", list(MASKS))
+@pytest.mark.parametrize("dense", [128, 384])
+def test_six_products_on_a_mask(name, dense):
+    import paper_2211_15841_amd as dm
+    rng = np.random.default_rng(zlib.crc32(("%s/%d" % (name, dense)).encode()))
+    mask = MASKS[name](rng)
+    if not mask.any():
+        mask[0, 0] = 1
+    R, C = mask.shape
+    M, N, D = R * 128, C * 128, dense
+    nnz = int(mask.sum())
+    xb, x = _bf16(rng, (M, D))
+    wdn_b, wdn = _bf16(rng, (D, N), 0.05)
+    wnd_b, wnd = _bf16(rng, (N, D), 0.05)
+    sb, s = _bf16(rng, (nnz, 128, 128))
+    bs = dm.BlockSparse(mask)
+    assert bs.nnz == nnz
+    xd, wdn_d, wnd_d, sd = _dev(xb), _dev(wdn_b), _dev(wnd_b), _dev(sb)
+
+    _close(_host(bs.sdd(xd, wdn_d)), bo.sdd(x, wdn, mask), "SDD")
+    _close(_host(bs.sddt(xd, wnd_d)), bo.sddt(x, wnd, mask), "SDD^T")
+    _close(_host(bs.dsd(sd, wnd_d)), bo.dsd(s, wnd, mask), "DSD")
+    _close(_host(bs.dsdt(sd, wdn_d)), bo.dsdt(s, wdn, mask), "DSD^T")
+    _close(_host(bs.dstd(sd, xd)), bo.dstd(s, x, mask), "DS^TD")
+    _close(_host(bs.ddts(xd, sd)), bo.ddts(x, s, mask), "DD^TS")
+
+    # rows / columns without blocks must come out as exact zeros
+    y = _host(bs.dsd(sd, wnd_d))
+    for r in np.nonzero(~mask.any(axis=1))[0]:
+        assert not y[r * 128:(r + 1) * 128].any()
+    z = _host(bs.dstd(sd, xd))
+    for c in np.nonzero(~mask.any(axis=0))[0]:
+        assert not z[c * 128:(c + 1) * 128].any()
+
+
+def test_topology_of_a_mask_is_bit_exact():
+    """The uploaded encoding equals the oracle's generic encoder (oracle.dmoe_oracle.encode_mask) on the same mask."""
+    import torch
+    import paper_2211_15841_amd as dm
+    from oracle import dmoe_oracle as orc
+    rng = np.random.default_rng(77)
+    mask = (rng.random((9, 11)) < 0.35).astype(np.uint8)
+    bs = dm.BlockSparse(mask)
+    enc = orc.encode_mask(mask.astype(bool))
+    raw = bs.topology_mem.cpu().numpy()
+
+    def arr(ptr_field, n):
+        off = getattr(bs.topo, ptr_field) - bs.topology_mem.data_ptr()
+        return raw[off:off + 4 * n].view(np.int32)
+    nnz = bs.nnz
+    np.testing.assert_array_equal(arr("row_offsets", mask.shape[0] + 1), enc["row_offsets"])
+    np.testing.assert_array_equal(arr("column_indices", nnz), enc["column_indices"])
+    np.testing.assert_array_equal(arr("row_indices", nnz), enc["row_indices"])
+    np.testing.assert_array_equal(arr("column_offsets_t", mask.shape[1] + 1), enc["column_offsets_t"])
+    np.testing.assert_array_equal(arr("row_indices_t", nnz), enc["row_indices_t"])
+    np.testing.assert_array_equal(arr("block_offsets_t", nnz), enc["block_offsets_t"])
