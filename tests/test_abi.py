@@ -78,3 +78,29 @@ def test_tile_mode_is_validated():
     dm.dmoe_set_tile_mode(0)
     with pytest.raises(dm.DMoEError, match="tile mode"):
         dm.dmoe_set_tile_mode(3)
+
+
+def test_general_products_validate_their_arguments():
+    """dmoe_bsmm_sizes / dmoe_bsmm_topology / dmoe_bsmm reject bad dimensions and pointers before touching the GPU."""
+    assert dm.dmoe_bsmm_sizes(4, 5, 7) % 256 == 0
+    assert dm.dmoe_bsmm_sizes(40, 50, 2000) >= dm.dmoe_bsmm_sizes(40, 50, 0) + 4 * 4 * 2000
+    for rows, cols, nnz, frag in [(0, 3, 0, "block_rows"), (3, 0, 0, "block_cols"), (2, 2, 5, "nnz"),
+                                  (2, 2, -1, "nnz"), (1 << 17, 1, 0, "2^24")]:
+        with pytest.raises(dm.DMoEError) as e:
+            dm.dmoe_bsmm_sizes(rows, cols, nnz)
+        assert frag in str(e.value)
+    lib = dm.load_library()
+    topo = dm.DMoETopology()
+    mask = (ctypes.c_uint8 * 4)(1, 0, 0, 1)
+    assert lib.dmoe_bsmm_topology(None, 2, 2, 256, 4096, ctypes.byref(topo), None) != 0          # NULL mask
+    assert lib.dmoe_bsmm_topology(mask, 2, 2, None, 4096, ctypes.byref(topo), None) != 0          # NULL device buffer
+    assert lib.dmoe_bsmm_topology(mask, 2, 2, 256 + 8, 4096, ctypes.byref(topo), None) != 0       # misaligned
+    assert lib.dmoe_bsmm_topology(mask, 2, 2, 256, 16, ctypes.byref(topo), None) != 0             # too small
+    assert "needs" in dm.dmoe_last_error()
+    assert lib.dmoe_bsmm(9, ctypes.byref(topo), 2, 2, 128, 256, 256, 256, None) != 0              # unknown product
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 128, 256, 256, 256, None) != 0      # topology not built
+    topo.row_offsets = 256
+    topo.counts = 256
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 100, 256, 256, 256, None) != 0      # dense not a multiple
+    assert "multiple of 128" in dm.dmoe_last_error()
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 128, None, 256, 256, None) != 0     # NULL operand
