@@ -83,7 +83,7 @@ def test_tile_mode_is_validated():
 def test_general_products_validate_their_arguments():
     """dmoe_bsmm_sizes / dmoe_bsmm_topology / dmoe_bsmm reject bad dimensions and pointers before touching the GPU."""
     assert dm.dmoe_bsmm_sizes(4, 5, 7) % 256 == 0
-    assert dm.dmoe_bsmm_sizes(40, 50, 2000) >= dm.dmoe_bsmm_sizes(40, 50, 0) + 4 * 4 * 2000
+    assert dm.dmoe_bsmm_sizes(40, 50, 2000) >= 4 * 4 * 2000 + 4 * (40 + 1) + 4 * (50 + 1)   # four arrays per block
     for rows, cols, nnz, frag in [(0, 3, 0, "block_rows"), (3, 0, 0, "block_cols"), (2, 2, 5, "nnz"),
                                   (2, 2, -1, "nnz"), (1 << 17, 1, 0, "2^24")]:
         with pytest.raises(dm.DMoEError) as e:
