@@ -219,7 +219,8 @@ __global__ void __launch_bounds__(256) chunk_hist_kernel(const int32_t* __restri
 
 // Single workgroup.  Turns chunk_counts into exclusive per-expert bases (in place), and writes
 // tokens_per_expert, padded_offsets (rows per expert = ceil(n_e/128)*128, Section 5.2), counts and expert_order.
-__global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
+constexpr int kOffsetsThreads = 1024;          // threads of the one workgroup: up to 1024 / E lanes per expert
+__global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
                                                               int db, int32_t* __restrict__ sched,
                                                        int32_t* __restrict__ tokens_per_expert,
                                                        int32_t* __restrict__ padded_offsets, int32_t* __restrict__ counts,
@@ -228,13 +229,13 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
   __shared__ int n_s[kMaxExperts];
   __shared__ int scan_s[kMaxExperts];
   __shared__ int gscan_s[kMaxExperts];
-  __shared__ int part_s[kMaxExperts];
+  __shared__ int part_s[kOffsetsThreads];
   const int tid = threadIdx.x;
   // L threads share one expert's column of chunk_counts: each sums a contiguous range of chunks, the ranges are
   // scanned through LDS, then each thread rewrites its range as exclusive bases.
   int epow = 1;
   while (epow < E) epow <<= 1;
-  const int L = kMaxExperts / epow;
+  const int L = kOffsetsThreads / epow;
   const int ex = tid % epow, part = tid / epow;
   const int per = (nchunks + L - 1) / L;
   const int cb = min(nchunks, part * per), ce = min(nchunks, cb + per);
@@ -261,16 +262,21 @@ __global__ void __launch_bounds__(kMaxExperts) offsets_kernel(int32_t* __restric
   if (tid >= E) n = 0;                      // threads 0..E-1 (part 0, ex == tid) own expert tid from here on
   if (tid < E) tokens_per_expert[tid] = n;
   const int padded = ((n + kBlock - 1) / kBlock) * kBlock;
-  n_s[tid] = n;
-  scan_s[tid] = tid < E ? padded : 0;
-  gscan_s[tid] = tid < E ? (padded / kBlock + 1) / 2 : 0;   // row groups: block-rows taken two at a time
+  const bool slot = tid < kMaxExperts;      // the per-expert arrays have kMaxExperts entries
+  if (slot) {
+    n_s[tid] = n;
+    scan_s[tid] = tid < E ? padded : 0;
+    gscan_s[tid] = tid < E ? (padded / kBlock + 1) / 2 : 0;   // row groups: block-rows taken two at a time
+  }
   __syncthreads();
   for (int off = 1; off < kMaxExperts; off <<= 1) {       // inclusive Hillis-Steele scans over experts
-    const int add = tid >= off ? scan_s[tid - off] : 0;
-    const int gadd = tid >= off ? gscan_s[tid - off] : 0;
+    const int add = (slot && tid >= off) ? scan_s[tid - off] : 0;
+    const int gadd = (slot && tid >= off) ? gscan_s[tid - off] : 0;
     __syncthreads();
-    scan_s[tid] += add;
-    gscan_s[tid] += gadd;
+    if (slot) {
+      scan_s[tid] += add;
+      gscan_s[tid] += gadd;
+    }
     __syncthreads();
   }
   if (tid < E) { padded_offsets[tid + 1] = scan_s[tid];  group_offsets[tid + 1] = gscan_s[tid]; }
@@ -441,7 +447,7 @@ void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_
   const int hb = c.ffn_hidden / kBlock;
   hipLaunchKernelGGL(chunk_hist_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts);
-  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kMaxExperts), 0, s, chunk_counts, nchunks, E, hb,
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kOffsetsThreads), 0, s, chunk_counts, nchunks, E, hb,
                      c.d_model / kBlock, t.sched, t.tokens_per_expert,
                      t.padded_offsets, t.counts, t.expert_order, t.group_offsets);
   hipLaunchKernelGGL(rank_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
