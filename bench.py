@@ -38,6 +38,8 @@ MEASURED_TRAFFIC = {
     ("small_zipf1.0", "dstd"): 980830003, ("small_zipf1.0", "dsdt"): 542817485, ("small_zipf1.0", "ddts"): 981277491,
     ("medium_zipf1.2_top2", "sdd"): 2360531149, ("medium_zipf1.2_top2", "dsd"): 2597010432, ("medium_zipf1.2_top2", "sddt"): 2363080090,
     ("medium_zipf1.2_top2", "dstd"): 2839578419, ("medium_zipf1.2_top2", "dsdt"): 2618286285, ("medium_zipf1.2_top2", "ddts"): 2875448934,
+    ("large_expert_top2", "sdd"): 16602969498, ("large_expert_top2", "dsd"): 14576305152, ("large_expert_top2", "sddt"): 18105627034,
+    ("large_expert_top2", "dstd"): 13386441933, ("large_expert_top2", "dsdt"): 15569899315, ("large_expert_top2", "ddts"): 22778809549,
 }
 
 
