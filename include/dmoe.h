@@ -189,6 +189,12 @@ DMOE_API int dmoe_bsmm_topology(const uint8_t *mask, int block_rows, int block_c
 DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int block_cols, int dense, const void *a,
                        const void *b, void *out, void *stream);
 
+/* Measurement aid: runs a register-only loop of v_mfma_f32_32x32x16_bf16 (four waves per SIMD on 256 CUs, no memory
+ * traffic) on `stream`, waits for it (this call SYNCHRONISES) and returns the rate in TFLOP/s: the matrix-pipe peak
+ * this device delivers at the clock it sustains, to set beside the published 2.5 PFLOP/s.  `scratch4`: device, >= 4
+ * bytes, 256-byte aligned (never written).  Errors: DMOE_EINVAL, DMOE_ELAUNCH.                                  */
+DMOE_API int dmoe_probe_mfma_tflops(float *tflops, void *scratch4, void *stream);
+
 /* Message for the last error returned on this thread (host pointer to static thread-local storage). */
 DMOE_API const char *dmoe_last_error(void);
 

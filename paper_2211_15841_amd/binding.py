@@ -67,10 +67,11 @@ def load_library() -> ctypes.CDLL:
                                        POINTER(DMoETopology), POINTER(c_int32)]
     lib.dmoe_bsmm.argtypes = [ctypes.c_int, POINTER(DMoETopology), ctypes.c_int, ctypes.c_int, ctypes.c_int, c_void_p,
                               c_void_p, c_void_p, c_void_p]
+    lib.dmoe_probe_mfma_tflops.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
                  "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
-                 "dmoe_bsmm_topology", "dmoe_bsmm"):
+                 "dmoe_bsmm_topology", "dmoe_bsmm", "dmoe_probe_mfma_tflops"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -203,6 +204,14 @@ class BlockSparse:
         out = self._out(x.shape[1], self.cols * 128)
         dmoe_bsmm(OP_DDTS, self.topo, self.rows, self.cols, x.shape[1], x, s, out, stream)
         return out
+
+
+def dmoe_probe_mfma_tflops(stream=None) -> float:
+    """bf16 MFMA rate of a register-only loop on this device, TFLOP/s (synchronises)."""
+    out = ctypes.c_float()
+    scratch = torch.zeros(64, dtype=torch.float32, device="cuda")
+    _check(load_library().dmoe_probe_mfma_tflops(byref(out), _ptr(scratch), _stream(stream)))
+    return out.value
 
 
 def dmoe_set_tile_mode(mode: int):

@@ -37,6 +37,23 @@ static int check_mask_dims(int R, int C, int nnz) {
   return DMOE_OK;
 }
 
+// Register-only MFMA loop: every wave keeps eight independent 32x32 accumulators busy with the instruction the
+// block-sparse products use; nothing touches memory until the one store that keeps the results alive.
+__global__ void __launch_bounds__(256) mfma_peak_kernel(float* sink, int iters) {
+  bf16x8_v a, b;
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(float)((threadIdx.x + i) & 3);  b[i] = (__bf16)0.5f; }
+  f32x16_v acc[8];
+  for (int j = 0; j < 8; ++j)
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.0f;
+  for (int j = 0; j < 8; ++j) s += acc[j][0] + acc[j][15];
+  if (s == -1.0f) sink[0] = s;                        // never true: the products are non-negative
+}
+
 }  // namespace dmoe
 
 using namespace dmoe;
@@ -141,6 +158,30 @@ int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_col
   }
   (void)hipGetLastError();
   launch_bsmm(static_cast<BsOp>(op), g, static_cast<hipStream_t>(stream));
+  return launch_status();
+}
+
+int dmoe_probe_mfma_tflops(float* tflops, void* scratch4, void* stream) {
+  if (!tflops) return fail(DMOE_EINVAL, "tflops is NULL");
+  if (int rc = check_ptr(scratch4, "scratch4")) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return fail(DMOE_ELAUNCH, "hipEventCreate failed");
+  const int grid = 256 * 4, iters = 4096;             // four workgroups of four waves per CU: four waves per SIMD
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(grid), dim3(256), 0, s, static_cast<float*>(scratch4), 64);   // warm-up
+  (void)hipEventRecord(e0, s);
+  hipLaunchKernelGGL(mfma_peak_kernel, dim3(grid), dim3(256), 0, s, static_cast<float*>(scratch4), iters);
+  (void)hipEventRecord(e1, s);
+  float ms = 0.0f;
+  hipError_t err = hipEventSynchronize(e1);
+  if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (err != hipSuccess || ms <= 0.0f) return fail(DMOE_ELAUNCH, "timing the probe failed: %s", hipGetErrorString(err));
+  const double flops = (double)grid * 4 /* waves */ * iters * 8 /* MFMAs */ * (2.0 * 32 * 32 * 16);
+  *tflops = (float)(flops / (ms * 1e-3) / 1e12);
   return launch_status();
 }
 
