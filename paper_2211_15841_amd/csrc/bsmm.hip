@@ -50,6 +50,7 @@ struct BsParams {
   const int32_t* expert_order;
   const int32_t* counts;
   const int32_t* sched;
+  const int32_t* tokens_per_expert;   // dMoE topologies only (NULL for a general mask): lets the weight gradients skip padding
   int d, h, E, hb, db;
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
@@ -198,6 +199,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     first0 = p.column_offsets_t[c0];
     first1 = p.column_offsets_t[c1];
     nk = kSub * (p.column_offsets_t[c0 + 1] - first0);
+    // The rows of an expert beyond its token count are padding (Section 5.2): zero in both operands of a weight
+    // gradient, so K tiles that lie entirely in the padding of the last block are skipped.
+    if (p.tokens_per_expert) nk = min(nk, (p.tokens_per_expert[e] + BK - 1) / BK);
     if constexpr (OP == OP_DSTD) { a_ok[1] = second_col;  b_ok[1] = second_d; }
     else                         { a_ok[1] = second_d;    b_ok[1] = second_col; }
   }
@@ -218,7 +222,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // that the barrier releases, with every wave waiting.
   int ix0 = 0, ix1 = 0, ix2 = 0;
   auto refill = [&](int kb0) {
-    const int n = nk / kSub - kb0;                  // blocks left from kb0 on
+    const int n = (nk + kSub - 1) / kSub - kb0;     // blocks left from kb0 on (the last one may be cut short)
     if (lane < n) {
       if constexpr (OP == OP_DSD || OP == OP_DSDT) {
         ix0 = p.column_indices[first0 + kb0 + lane];
@@ -524,6 +528,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.column_offsets_t = t.column_offsets_t;  p.row_indices_t = t.row_indices_t;  p.block_offsets_t = t.block_offsets_t;
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.counts = t.counts;  p.sched = t.sched;
+  p.tokens_per_expert = a.plain ? nullptr : t.tokens_per_expert;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   p.plain = a.plain;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
