@@ -53,7 +53,8 @@ def test_small_cases(cfg):
     [128, 256, 0, 128, 384, 128],      # exact multiples of the block, one empty expert
     [127, 129, 1, 255, 257, 0],        # one under / one over the block boundary
     [0, 0, 0, 700, 0, 0],              # one expert takes everything
-], ids=["exact_blocks", "block_pm1", "one_takes_all"])
+    [63, 64, 65, 191, 192, 193],       # around the 64-row K tiles: the weight gradients skip all-padding K tiles
+], ids=["exact_blocks", "block_pm1", "one_takes_all", "half_block_pm1"])
 def test_forced_expert_loads(counts):
     E = len(counts)
     assignment = np.repeat(np.arange(E), counts)
