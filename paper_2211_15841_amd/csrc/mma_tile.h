@@ -19,6 +19,7 @@ enum Layout { KC = 0, NC = 1 };
 // (BK = 32: rows are 64 bytes, four rows share a 256-byte bank line, and the swizzle is c ^ ((r >> 2) & 3).)
 template <int BK>
 __device__ __forceinline__ int kc_offset(int row, int chunk) {
+  static_assert(BK == 32 || BK == 64, "unsupported K tile");
   if constexpr (BK == 64) return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
   else                    return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4);
 }
@@ -34,6 +35,7 @@ typedef __attribute__((address_space(1))) const void* glb_void_ptr;
 // the element offset (relative to the slab's base pointer) that lane `lane` must fetch for 1 KB chunk `ch`.
 template <int L, int BK>
 __device__ __forceinline__ uint32_t dma_lane_offset(int ch, int lane, uint32_t ld) {
+  static_assert(BK == 32 || BK == 64, "unsupported K tile");
   if constexpr (L == KC && BK == 64) {         // chunk = 8 rows x 128 B
     const int row = 8 * ch + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
