@@ -82,7 +82,7 @@ def algorithmic_bytes(stage: str, T, k, d, h, E, P, active) -> float:
     }[stage]
 
 
-def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True):
+def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=False):
     import numpy as np
     import torch
     import paper_2211_15841_amd as dm
@@ -100,10 +100,18 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True):
     bias = torch.from_numpy(inp["router_bias"]).cuda() if inp["router_bias"] is not None else None
     ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk)
 
+    if accumulate:     # fp32 accumulators of a training loop with gradient accumulation (never zeroed here: timing only)
+        acc = [torch.zeros(s_, dtype=torch.float32, device="cuda")
+               for s_ in ((cfg.d_model, cfg.num_experts), (cfg.d_model, cfg.num_experts * cfg.ffn_hidden),
+                          (cfg.num_experts * cfg.ffn_hidden, cfg.d_model))]
+
     def step():
         ws.topology(x, wr, bias)
         ws.forward(x, w1, w2)
-        ws.backward(x, wr, w1, w2, dy)
+        if accumulate:
+            ws.backward_accumulate(x, wr, w1, w2, dy, *acc)
+        else:
+            ws.backward(x, wr, w1, w2, dy)
 
     nst = len(dm.STAGE_NAMES)
     EvArr = ctypes.c_void_p * (2 * nst)
@@ -208,6 +216,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2),
                     help="0: the library's own tile choice (default); 1 / 2: force 128x128 / 256x256 tiles (experiments)")
+    ap.add_argument("--accumulate", action="store_true",
+                    help="time dmoe_backward_accumulate (fp32 weight-gradient accumulators) instead of dmoe_backward; "
+                         "a variant for context, not the headline step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -237,10 +248,11 @@ def main():
     measured_peak = dm.dmoe_probe_mfma_tflops()       # register-only MFMA loop on this machine (context for % of peak)
     hipev = HipEvents()
     cfg = pick(args.config)
-    main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu)
+    main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu, accumulate=args.accumulate)
     others = []
     for name in [n for n in args.also.split(",") if n and n != cfg.name]:
-        others.append(run_config(pick(name), max(5, args.steps // 5), max(4, args.warmup // 2), hipev, with_cpu=False))
+        others.append(run_config(pick(name), max(5, args.steps // 5), max(4, args.warmup // 2), hipev, with_cpu=False,
+                                 accumulate=args.accumulate))
 
     line = {
         "metric": "dMoE FFN fwd+bwd useful TFLOP/s (bf16) + % MFMA peak, 1 MI355X",
@@ -250,6 +262,7 @@ def main():
         "config": {"workload": cfg.name, "num_tokens": cfg.num_tokens, "d_model": cfg.d_model,
                    "ffn_hidden": cfg.ffn_hidden, "num_experts": cfg.num_experts, "top_k": cfg.top_k,
                    "block": 128, "routing": "zipf(%.1f)-biased router" % cfg.zipf_s if cfg.zipf_s else "random router"},
+        "backward": "dmoe_backward_accumulate (fp32 accumulators)" if args.accumulate else "dmoe_backward",
         "pct_mfma_peak": main_res["pct_mfma_peak"],
         "mfma_peak_measured_tflops": round(measured_peak, 1),
         "pct_mfma_peak_measured": round(100.0 * main_res["useful_tflops"] / measured_peak, 2),

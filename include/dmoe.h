@@ -16,7 +16,8 @@
  * Conventions
  *   - Every pointer named below is a DEVICE pointer into caller-owned memory unless it says "host".
  *     The library allocates no device memory, frees none, and keeps no device state between calls.
- *   - Every device buffer must be 256-byte aligned.  Outputs are overwritten (never accumulated into).
+ *   - Every device buffer must be 256-byte aligned.  Outputs are overwritten (never accumulated into), except
+ *     the three accumulators of dmoe_backward_accumulate.
  *   - dmoe_topology / dmoe_forward / dmoe_backward only enqueue work on `stream` (a hipStream_t passed as
  *     void*; NULL = the null stream).  They never synchronise and never copy to the host: the padded row
  *     count P and the number of nonzero blocks live in device memory (dmoe_topology_t.counts) and the
@@ -124,6 +125,16 @@ DMOE_API int dmoe_backward(const dmoe_config *cfg, const void *x, const void *w_
                   const dmoe_topology_t *topo, const void *saved, size_t saved_bytes, const void *dy,
                   void *dx, void *dw_router, void *dw1, void *dw2,
                   void *scratch, size_t scratch_bytes, void *stream);
+
+/* The same backward pass for training with gradient accumulation over micro-batches (Section 6.2 trains every
+ * model that way): the three weight gradients are ADDED, in fp32, to caller-owned fp32 accumulators
+ * dw_router_acc [d,E], dw1_acc [d,E*h] and dw2_acc [E*h,d] (the products' fp32 sums are added without being
+ * rounded to bf16 first; the caller zeroes the accumulators before the first micro-batch).  dx is written as in
+ * dmoe_backward.  Slices of experts with no tokens are left as they are.  Same errors as dmoe_backward.        */
+DMOE_API int dmoe_backward_accumulate(const dmoe_config *cfg, const void *x, const void *w_router, const void *w1,
+                             const void *w2, const dmoe_topology_t *topo, const void *saved, size_t saved_bytes,
+                             const void *dy, void *dx, float *dw_router_acc, float *dw1_acc, float *dw2_acc,
+                             void *scratch, size_t scratch_bytes, void *stream);
 
 /* Test helper: waits for `stream` and copies counts[4] (P, R, nnz, 0) to host memory `out4`. */
 DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out4, void *stream);

@@ -59,6 +59,7 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_backward.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, c_void_p, POINTER(DMoETopology),
                                   c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                   c_size_t, c_void_p]
+    lib.dmoe_backward_accumulate.argtypes = lib.dmoe_backward.argtypes
     lib.dmoe_topology_counts_host.argtypes = [POINTER(DMoETopology), POINTER(c_int32), c_void_p]
     lib.dmoe_set_stage_events.argtypes = [c_void_p]
     lib.dmoe_set_tile_mode.argtypes = [ctypes.c_int]
@@ -70,7 +71,7 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_probe_mfma_tflops.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
-                 "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
+                 "dmoe_backward_accumulate", "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
                  "dmoe_bsmm_topology", "dmoe_bsmm", "dmoe_probe_mfma_tflops"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -129,6 +130,17 @@ def dmoe_backward(cfg, x, w_router, w1, w2, topo, saved, saved_bytes, dy, dx, dw
     _check(load_library().dmoe_backward(byref(cfg), _ptr(x), _ptr(w_router), _ptr(w1), _ptr(w2), byref(topo),
                                         _ptr(saved), saved_bytes, _ptr(dy), _ptr(dx), _ptr(dw_router), _ptr(dw1),
                                         _ptr(dw2), _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def dmoe_backward_accumulate(cfg, x, w_router, w1, w2, topo, saved, saved_bytes, dy, dx, dw_router_acc, dw1_acc,
+                             dw2_acc, scratch, scratch_bytes, stream=None):
+    for name, t in (("dw_router_acc", dw_router_acc), ("dw1_acc", dw1_acc), ("dw2_acc", dw2_acc)):
+        if t.dtype != torch.float32:
+            raise TypeError("%s must be float32 (got %s)" % (name, t.dtype))
+    _check(load_library().dmoe_backward_accumulate(byref(cfg), _ptr(x), _ptr(w_router), _ptr(w1), _ptr(w2),
+                                                   byref(topo), _ptr(saved), saved_bytes, _ptr(dy), _ptr(dx),
+                                                   _ptr(dw_router_acc), _ptr(dw1_acc), _ptr(dw2_acc), _ptr(scratch),
+                                                   scratch_bytes, _stream(stream)))
 
 
 def dmoe_topology_counts_host(topo, stream=None):
@@ -257,6 +269,13 @@ class Workspace:
         dmoe_backward(self.cfg, x, w_router, w1, w2, self.topo, self.saved, self.sizes["saved_bytes"], dy, self.dx,
                       self.dw_router, self.dw1, self.dw2, self.scratch, self.sizes["scratch_bytes"], stream)
         return self.dx, self.dw_router, self.dw1, self.dw2
+
+    def backward_accumulate(self, x, w_router, w1, w2, dy, dw_router_acc, dw1_acc, dw2_acc, stream=None):
+        """Backward pass that adds the weight gradients to the caller's fp32 accumulators; returns dx."""
+        dmoe_backward_accumulate(self.cfg, x, w_router, w1, w2, self.topo, self.saved, self.sizes["saved_bytes"], dy,
+                                 self.dx, dw_router_acc, dw1_acc, dw2_acc, self.scratch, self.sizes["scratch_bytes"],
+                                 stream)
+        return self.dx
 
     # -- read-back of the topology arrays (tests) ----------------------------------------------------------
     def topology_arrays(self) -> dict:

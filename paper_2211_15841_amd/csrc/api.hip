@@ -250,9 +250,13 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
   return launch_status();
 }
 
-int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, const void* w1, const void* w2,
-                  const dmoe_topology_t* topo, const void* saved, size_t saved_bytes, const void* dy, void* dx,
-                  void* dw_router, void* dw1, void* dw2, void* scratch, size_t scratch_bytes, void* stream) {
+// dmoe_backward (accumulate = 0: bf16 weight gradients, overwritten) and dmoe_backward_accumulate (accumulate = 1:
+// fp32 weight gradients, added to) differ only in the epilogue of the two weight-gradient products and in the last
+// kernel of the router's gradient.
+static int backward_impl(const dmoe_config* cfg, const void* x, const void* w_router, const void* w1, const void* w2,
+                         const dmoe_topology_t* topo, const void* saved, size_t saved_bytes, const void* dy, void* dx,
+                         void* dw_router, void* dw1, void* dw2, void* scratch, size_t scratch_bytes, void* stream,
+                         int accumulate) {
   Dims m;
   if (int rc = check_config(cfg, &m)) return rc;
   if (int rc = check_ptr(x, "x")) return rc;
@@ -302,7 +306,9 @@ int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, c
 
   ev.begin(DMOE_STAGE_DSTD);   // dW2 = A^T dYp
   a.dense_a = dyp; a.dense_b = nullptr; a.sparse_in = aval; a.out0 = static_cast<bf16_t*>(dw2);
+  a.accum = accumulate;
   launch_bsmm(OP_DSTD, a, s);
+  a.accum = 0;
   ev.end(DMOE_STAGE_DSTD);
 
   ev.begin(DMOE_STAGE_DSDT);   // dXp = dH W1^T
@@ -312,14 +318,31 @@ int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, c
 
   ev.begin(DMOE_STAGE_DDTS);   // dW1 = Xp^T dH
   a.dense_a = xp; a.dense_b = nullptr; a.sparse_in = dh; a.out0 = static_cast<bf16_t*>(dw1);
+  a.accum = accumulate;
   launch_bsmm(OP_DDTS, a, s);
+  a.accum = 0;
   ev.end(DMOE_STAGE_DDTS);
 
   ev.begin(DMOE_STAGE_ROUTER_BWD);
   launch_router_bwd(*cfg, *topo, static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w_router), dweights, dxp,
-                    dlogits, partials, m.npart, static_cast<bf16_t*>(dx), static_cast<float*>(dw_router), s);
+                    dlogits, partials, m.npart, static_cast<bf16_t*>(dx), static_cast<float*>(dw_router), accumulate != 0, s);
   ev.end(DMOE_STAGE_ROUTER_BWD);
   return launch_status();
+}
+
+int dmoe_backward(const dmoe_config* cfg, const void* x, const void* w_router, const void* w1, const void* w2,
+                  const dmoe_topology_t* topo, const void* saved, size_t saved_bytes, const void* dy, void* dx,
+                  void* dw_router, void* dw1, void* dw2, void* scratch, size_t scratch_bytes, void* stream) {
+  return backward_impl(cfg, x, w_router, w1, w2, topo, saved, saved_bytes, dy, dx, dw_router, dw1, dw2, scratch,
+                       scratch_bytes, stream, 0);
+}
+
+int dmoe_backward_accumulate(const dmoe_config* cfg, const void* x, const void* w_router, const void* w1,
+                             const void* w2, const dmoe_topology_t* topo, const void* saved, size_t saved_bytes,
+                             const void* dy, void* dx, float* dw_router_acc, float* dw1_acc, float* dw2_acc,
+                             void* scratch, size_t scratch_bytes, void* stream) {
+  return backward_impl(cfg, x, w_router, w1, w2, topo, saved, saved_bytes, dy, dx, dw_router_acc, dw1_acc, dw2_acc,
+                       scratch, scratch_bytes, stream, 1);
 }
 
 int dmoe_topology_counts_host(const dmoe_topology_t* topo, int32_t* out4, void* stream) {

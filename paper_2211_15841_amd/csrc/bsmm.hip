@@ -56,6 +56,7 @@ struct BsParams {
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
   int items;               // work items of this launch (weight gradients: may exceed the grid)
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
+  int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
 };
 
 template <int OP> struct OpLayouts;
@@ -418,6 +419,36 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   } else {
     out = p.out0 + ((size_t)(jd0 + pm) * kBlock + arow0) * ldw + (size_t)(pn ? c1 : c0) * kBlock + hn * 64;  ldo = ldw;
   }
+  if constexpr (!kRowMajor) {
+    if (p.accum) {
+      // fp32 accumulation: out0 is an fp32 matrix of the same shape.  The staging tile holds 32 columns at a time
+      // (128-byte rows again), so every load and store below covers whole 128-byte row segments.  The tile belongs
+      // to this workgroup alone, so a plain read-modify-write is enough.
+      float* outf = reinterpret_cast<float*>(p.out0) + (out - p.out0);
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float4 v;
+            v.x = acc[i][jj][4 * q + 0];  v.y = acc[i][jj][4 * q + 1];
+            v.z = acc[i][jj][4 * q + 2];  v.w = acc[i][jj][4 * q + 3];
+            *reinterpret_cast<float4*>(ep + kc_offset<64>(32 * i + (lane & 31), 2 * q + (lane >> 5))) = v;
+          }
+#pragma unroll
+        for (int it = 0; it < 4 * MI; ++it) {
+          const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+          const float4 v = *reinterpret_cast<const float4*>(ep + kc_offset<64>(row, chunk));
+          float4* g = reinterpret_cast<float4*>(outf + (size_t)row * ldo + 32 * jj + chunk * 4);
+          float4 o = *g;
+          o.x += v.x;  o.y += v.y;  o.z += v.z;  o.w += v.w;
+          *g = o;
+        }
+      }
+      return;
+    }
+  }
   auto slot = [&](int i, int jj, int q) -> uint2* {          // this lane's 4 values of tile (i, jj), quad q
     return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * i + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
   };
@@ -563,6 +594,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.tokens_per_expert = a.plain ? nullptr : t.tokens_per_expert;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   p.plain = a.plain;
+  p.accum = a.accum;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless

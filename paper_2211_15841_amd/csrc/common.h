@@ -70,7 +70,7 @@ void launch_bwd_gather(const dmoe_config& c, const dmoe_topology_t& t, const bf1
                        bf16_t* dyp, float* dweights, int p_max, hipStream_t s);
 void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* x, const bf16_t* wr,
                        const float* dweights, const bf16_t* dxp, float* dlogits, float* partials, int num_partials,
-                       bf16_t* dx, float* dw_router, hipStream_t s);
+                       bf16_t* dx, float* dw_router, bool accumulate, hipStream_t s);
 int router_bwd_num_partials(const dmoe_config& c);
 
 enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5 };
@@ -81,6 +81,7 @@ struct BsArgs {
   int groups_est;          // T*k/256: row groups if the routing were perfectly packed (tile-size heuristic)
   int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
   int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
+  int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))

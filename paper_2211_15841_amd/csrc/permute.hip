@@ -369,7 +369,7 @@ __global__ void __launch_bounds__(256) dwr_mfma_kernel(const bf16_t* __restrict_
   }
 }
 __global__ void __launch_bounds__(256) dwr_reduce_kernel(const float* __restrict__ partials, int nchunks, int n,
-                                                         float* __restrict__ dwr) {
+                                                         float* __restrict__ dwr, int accumulate) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= n) return;
   float s = 0.0f;
@@ -382,7 +382,7 @@ __global__ void __launch_bounds__(256) dwr_reduce_kernel(const float* __restrict
     for (int u = 0; u < 8; ++u) s += v[u];
   }
   for (; c < nchunks; ++c) s += partials[(size_t)c * n + idx];
-  dwr[idx] = s;
+  dwr[idx] = accumulate ? dwr[idx] + s : s;
 }
 
 // ------------------------------------------------------------------------------------------------ launchers
@@ -411,7 +411,7 @@ int router_bwd_num_partials(const dmoe_config& c) {
 
 void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf16_t* x, const bf16_t* wr,
                        const float* dweights, const bf16_t* dxp, float* dlogits, float* partials, int num_partials,
-                       bf16_t* dx, float* dw_router, hipStream_t s) {
+                       bf16_t* dx, float* dw_router, bool accumulate, hipStream_t s) {
   const int T = c.num_tokens, d = c.d_model, E = c.num_experts, k = c.top_k;
   int g = 1;
   while (g < E && g < 64) g <<= 1;
@@ -439,7 +439,7 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
   hipLaunchKernelGGL(dwr_mfma_kernel, dim3(num_partials, d / 128), dim3(256), 0, s, x, dlogits, partials, T, d, E,
                      dwr_chunk_tokens(c));
   hipLaunchKernelGGL(dwr_reduce_kernel, dim3((d * E + 255) / 256), dim3(256), 0, s, partials, num_partials, d * E,
-                     dw_router);
+                     dw_router, accumulate ? 1 : 0);
 }
 
 }  // namespace dmoe

@@ -70,6 +70,12 @@ def test_bind_and_calls_validate_pointers_without_launching():
     rc = lib.dmoe_backward(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.byref(topo), fake, 8, fake, fake, fake,
                            fake, fake, fake, s["scratch_bytes"], None)
     assert rc == -2
+    rc = lib.dmoe_backward_accumulate(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.byref(topo), fake,
+                                      s["saved_bytes"], fake, fake, fake, None, fake, fake, s["scratch_bytes"], None)
+    assert rc == -1 and "dw1 is NULL" in dm.dmoe_last_error()
+    rc = lib.dmoe_backward_accumulate(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.byref(topo), fake, 8, fake,
+                                      fake, fake, fake, fake, fake, s["scratch_bytes"], None)
+    assert rc == -2
 
 
 def test_tile_mode_is_validated():

@@ -1,0 +1,96 @@
+"""dmoe_backward_accumulate (fp32 gradient accumulation over micro-batches) against the oracle and against
+dmoe_backward.
+
+What is checked: (1) accumulating one micro-batch into zeros and rounding to bf16 gives dmoe_backward's weight
+gradients bit for bit (same products, same summation order, only the epilogue differs), and dx is identical;
+(2) after two micro-batches on top of a non-zero starting value the accumulators equal start + g1 + g2 of the
+oracle within the layer's tolerance; (3) slices of experts that received no token keep their contents exactly;
+(4) the sum equals the oracle's gradient of the two micro-batches taken as one batch (the layer acts on every token
+independently, so this must hold)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2211_15841_amd as dm
+from dmoe_inputs import small_config, make_inputs
+from oracle import dmoe_oracle as orc
+from tests._harness import to_dev, check_values, run_oracle_indices
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_grads(cfg, inp):
+    ref = run_oracle_indices(cfg, inp)
+    g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], ref["expert_idx"], ref["weights"],
+                     ref["probs"], cfg.ffn_hidden, cfg.normalize_topk)
+    return g, ref
+
+
+@pytest.mark.parametrize("tile_mode", [0, 1, 2], ids=["auto", "tiles_128", "tiles_256"])
+@pytest.mark.parametrize("cfg", [
+    small_config("acc_k2", T=600, d=256, h=384, E=6, k=2, normalize_topk=1, zipf_s=1.0, seed=301),
+    small_config("acc_empty_experts", T=12, d=128, h=256, E=16, k=1, seed=302),
+], ids=lambda c: c.name)
+def test_two_micro_batches(cfg, tile_mode):
+    # two micro-batches: same weights, different tokens and upstream gradients
+    mb = [make_inputs(cfg), make_inputs(small_config(cfg.name, cfg.num_tokens, cfg.d_model, cfg.ffn_hidden,
+                                                     cfg.num_experts, cfg.top_k, cfg.normalize_topk, cfg.zipf_s,
+                                                     cfg.seed + 50))]
+    for key in ("w_router", "w1", "w2", "router_bias"):
+        mb[1][key] = mb[0][key]
+    d, h, E = cfg.d_model, cfg.ffn_hidden, cfg.num_experts
+    dm.dmoe_set_tile_mode(tile_mode)
+    try:
+        ws = dm.Workspace(cfg.num_tokens, d, h, E, cfg.top_k, cfg.normalize_topk)
+        w = {k: to_dev(mb[0][k]) for k in ("w_router", "w1", "w2")}
+        bias = torch.from_numpy(mb[0]["router_bias"]).cuda() if mb[0].get("router_bias") is not None else None
+        rng = np.random.default_rng(cfg.seed)
+        start = {"dw_router": rng.standard_normal((d, E)).astype(np.float32),
+                 "dw1": rng.standard_normal((d, E * h)).astype(np.float32),
+                 "dw2": rng.standard_normal((E * h, d)).astype(np.float32)}
+        acc = {k: torch.from_numpy(v).cuda() for k, v in start.items()}
+        zero = {k: torch.zeros_like(v) for k, v in acc.items()}
+        empty_everywhere = np.ones(E, bool)
+        sums = {k: v.astype(np.float64) for k, v in start.items()}
+        for i, inp in enumerate(mb):
+            x, dy = to_dev(inp["x"]), to_dev(inp["dy"])
+            ws.topology(x, w["w_router"], bias)
+            ws.forward(x, w["w1"], w["w2"])
+            dx, dwr, dw1, dw2 = [t.clone() for t in ws.backward(x, w["w_router"], w["w1"], w["w2"], dy)]
+            if i == 0:      # (1) one micro-batch into zeros == the bf16 path before its final rounding
+                dx_acc = ws.backward_accumulate(x, w["w_router"], w["w1"], w["w2"], dy, zero["dw_router"],
+                                                zero["dw1"], zero["dw2"]).clone()
+                torch.cuda.synchronize()
+                assert torch.equal(dx_acc.view(torch.int16), dx.view(torch.int16))
+                assert torch.equal(zero["dw1"].to(torch.bfloat16).view(torch.int16), dw1.view(torch.int16))
+                assert torch.equal(zero["dw2"].to(torch.bfloat16).view(torch.int16), dw2.view(torch.int16))
+                assert torch.equal(zero["dw_router"], dwr)
+            ws.backward_accumulate(x, w["w_router"], w["w1"], w["w2"], dy, acc["dw_router"], acc["dw1"], acc["dw2"])
+            torch.cuda.synchronize()
+            g, ref = _oracle_grads(cfg, inp)
+            empty_everywhere &= ref["tokens_per_expert"] == 0
+            for k in sums:
+                sums[k] += g[k]
+        got = {k: v.cpu().numpy().astype(np.float64) for k, v in acc.items()}
+        # (2) start + g1 + g2; the error is measured against the size of the gradients, not of the starting values
+        for k in ("dw1", "dw2", "dw_router"):
+            gsum = sums[k] - start[k]
+            if np.abs(gsum).max() > 1e-9:
+                check_values(k, got[k] - start[k], gsum)
+        # (3) experts without tokens in both micro-batches: untouched, bit for bit
+        for e in np.flatnonzero(empty_everywhere):
+            assert np.array_equal(got["dw1"][:, e * h:(e + 1) * h], start["dw1"][:, e * h:(e + 1) * h].astype(np.float64))
+            assert np.array_equal(got["dw2"][e * h:(e + 1) * h, :], start["dw2"][e * h:(e + 1) * h, :].astype(np.float64))
+        if cfg.name == "acc_empty_experts":
+            assert empty_everywhere.any(), "the case is meant to leave some expert without tokens"
+        # (4) the two micro-batches as one batch
+        both = small_config(cfg.name, 2 * cfg.num_tokens, d, h, E, cfg.top_k, cfg.normalize_topk, cfg.zipf_s, cfg.seed)
+        joined = dict(mb[0])
+        for key in ("x", "dy"):
+            joined[key] = np.concatenate([mb[0][key], mb[1][key]], axis=0)
+        gj, _ = _oracle_grads(both, joined)
+        for k in ("dw1", "dw2", "dw_router"):
+            if np.abs(gj[k]).max() > 1e-9:
+                check_values(k + " (joined)", got[k] - start[k], gj[k])
+    finally:
+        dm.dmoe_set_tile_mode(0)

@@ -225,3 +225,29 @@ def test_slices_equal_the_full_computation():
         a, b = orc.weight_grad_panel(inp["x"], inp["w1"], inp["w2"], inp["dy"], idx, w, h, e, cols)
         assert np.allclose(a, g["dw1"][:, e * h + np.array(cols)], rtol=1e-10, atol=1e-14)
         assert np.allclose(b, g["dw2"][e * h + np.array(cols), :], rtol=1e-10, atol=1e-14)
+
+
+def test_weight_gradients_add_up_over_micro_batches():
+    """Gradient accumulation (Section 6.2): the layer treats every token independently, so the weight gradients of
+    two micro-batches taken as one batch are the sum of the micro-batches' own gradients.  This pins what
+    dmoe_backward_accumulate is compared with (start + g1 + g2) to the oracle's single-batch gradient."""
+    from dmoe_inputs import small_config, make_inputs
+    cfg = small_config("mb", T=90, d=128, h=128, E=5, k=2, normalize_topk=1, zipf_s=0.8, seed=411)
+    a, b = make_inputs(cfg), make_inputs(small_config("mb", 90, 128, 128, 5, 2, 1, 0.8, 412))
+    for key in ("w_router", "w1", "w2", "router_bias"):
+        b[key] = a[key]
+
+    def grads(c, inp):
+        _, idx, w, p = orc.route(inp["x"], inp["w_router"], inp["router_bias"], c.top_k, c.normalize_topk)
+        return orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], idx, w, p, c.ffn_hidden,
+                            c.normalize_topk)
+
+    ga, gb = grads(cfg, a), grads(cfg, b)
+    joined = dict(a)
+    for key in ("x", "dy"):
+        joined[key] = np.concatenate([a[key], b[key]], axis=0)
+    gj = grads(small_config("mb", 180, 128, 128, 5, 2, 1, 0.8, 411), joined)
+    for k in ("dw1", "dw2", "dw_router"):
+        assert np.abs(gj[k]).max() > 0
+        assert np.allclose(ga[k] + gb[k], gj[k], rtol=1e-10, atol=1e-12 * np.abs(gj[k]).max()), k
+    assert np.allclose(np.concatenate([ga["dx"], gb["dx"]]), gj["dx"], rtol=1e-10, atol=1e-14)
