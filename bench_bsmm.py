@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
 """Throughput of the general block-sparse products (dmoe_bsmm) on a random 128x128 block mask: the six products
-of Sections 4.2 / 5.1 on a topology that is NOT block-diagonal.  One JSON line; flops = 2 * nnz * 128 * 128 * D.
+of Sections 4.2 / 5.1, and DDS, on a topology that is NOT block-diagonal.  One JSON line; flops = 2 * nnz * 128 * 128 * D.
 
     python bench_bsmm.py [--block-rows 64] [--block-cols 64] [--density 0.5] [--dense 1024] [--iters 20]
 """
@@ -40,9 +40,11 @@ def main():
     w_dn = (0.05 * torch.randn(D, N, device="cuda", generator=g)).to(torch.bfloat16)
     w_nd = (0.05 * torch.randn(N, D, device="cuda", generator=g)).to(torch.bfloat16)
     s = torch.randn(bs.nnz, 128, 128, device="cuda", generator=g).to(torch.bfloat16)
+    xt = torch.randn(D, M, device="cuda", generator=g).to(torch.bfloat16)
     ops = {
         "sdd": lambda: bs.sdd(x, w_dn), "dsd": lambda: bs.dsd(s, w_nd), "sddt": lambda: bs.sddt(x, w_nd),
         "dstd": lambda: bs.dstd(s, x), "dsdt": lambda: bs.dsdt(s, w_dn), "ddts": lambda: bs.ddts(x, s),
+        "dds": lambda: bs.dds(xt, s),
     }
     flops = 2.0 * bs.nnz * 128 * 128 * D
     out = {}

@@ -164,7 +164,7 @@ DMOE_API int dmoe_set_stage_events(void *events);
 DMOE_API int dmoe_set_tile_mode(int mode);
 
 /* ---- General block-sparse products (Sections 4.2, 5.1) ---------------------------------------------------------
- * The six products of the layer are general primitives on a 128x128 block-sparse matrix S of block_rows x block_cols
+ * The six products of the layer (and DDS, dense = dense x sparse, which the layer does not need) are general primitives on a 128x128 block-sparse matrix S of block_rows x block_cols
  * blocks with ANY mask; the dMoE topology is the block-diagonal instance.  These entry points expose them for a
  * caller-supplied mask, without the fused dMoE epilogues, one 128x128 block per workgroup.  Values of S: block b of
  * the row-wise order (ascending row, ascending column inside a row) is a contiguous row-major 128x128 bf16 tile at
@@ -178,8 +178,10 @@ DMOE_API int dmoe_set_tile_mode(int mode);
  *   DMOE_OP_DSTD  a = S         b = X [M,D]   out [N,D]  = S^T X      (through the transpose indices, Section 5.1.4)
  *   DMOE_OP_DSDT  a = S         b = W [D,N]   out [M,D]  = S W^T
  *   DMOE_OP_DDTS  a = X [M,D]   b = S         out [D,N]  = X^T S      (through the transpose indices)
+ *   DMOE_OP_DDS   a = X [D,M]   b = S         out [D,N]  = X S        (through the transpose indices; Section 5.1.1)
  */
-enum { DMOE_OP_SDD = 0, DMOE_OP_DSD = 1, DMOE_OP_SDDT = 2, DMOE_OP_DSTD = 3, DMOE_OP_DSDT = 4, DMOE_OP_DDTS = 5 };
+enum { DMOE_OP_SDD = 0, DMOE_OP_DSD = 1, DMOE_OP_SDDT = 2, DMOE_OP_DSTD = 3, DMOE_OP_DSDT = 4, DMOE_OP_DDTS = 5,
+       DMOE_OP_DDS = 6 };
 
 /* Bytes of device memory that the topology of a mask with `nnz` nonzero blocks needs (host pointer out).
  * Errors: DMOE_EINVAL (dimensions < 1, 128*dimension >= 2^24, nnz out of range).                               */
@@ -195,7 +197,7 @@ DMOE_API int dmoe_bsmm_topology(const uint8_t *mask, int block_rows, int block_c
 
 /* Enqueue one product (table above) on `stream`; asynchronous.  `topo` must come from dmoe_bsmm_topology with the same
  * block_rows and block_cols.  Rows of S without blocks give zero rows of the DSD / DSD^T output, columns without
- * blocks zero rows of the DS^TD output and zero columns of the DD^TS output.
+ * blocks zero rows of the DS^TD output and zero columns of the DD^TS / DDS output.
  * Errors: DMOE_EINVAL (unknown op, NULL or misaligned pointer, dense not a multiple of 128), DMOE_ELAUNCH.       */
 DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int block_cols, int dense, const void *a,
                        const void *b, void *out, void *stream);

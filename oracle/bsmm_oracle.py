@@ -10,6 +10,7 @@ present where `mask` is nonzero and absent (zero) elsewhere, the definitions are
     SDD   S = (X W)   restricted to the mask          SDD^T  S = (X W^T) restricted to the mask
     DSD   Y = S W                                      DSD^T  Y = S W^T
     DS^TD Y = S^T X                                    DD^TS  Y = X^T S
+    DDS   Y = X S     (dense output, sparse right input; named in Section 5.1.1, not used by the layer)
 
 and that is what this file writes out: densify, multiply in float64, restrict.  The values of S travel as
 [nnz, 128, 128] in the row-wise order of the nonzero blocks (ascending row, ascending column inside a row), which is
@@ -81,3 +82,8 @@ def dstd(s: np.ndarray, x: np.ndarray, mask: np.ndarray) -> np.ndarray:
 def ddts(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
     """Y = X^T S.  x [M, D], Y [D, N]."""
     return x.astype(np.float64).T @ densify(s.astype(np.float64), mask)
+
+
+def dds(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Y = X S.  x [D, M], Y [D, N]."""
+    return x.astype(np.float64) @ densify(s.astype(np.float64), mask)

@@ -149,7 +149,7 @@ def dmoe_topology_counts_host(topo, stream=None):
     return list(out)
 
 
-OP_SDD, OP_DSD, OP_SDDT, OP_DSTD, OP_DSDT, OP_DDTS = range(6)
+OP_SDD, OP_DSD, OP_SDDT, OP_DSTD, OP_DSDT, OP_DDTS, OP_DDS = range(7)
 
 
 def dmoe_bsmm_sizes(block_rows: int, block_cols: int, nnz: int) -> int:
@@ -215,6 +215,13 @@ class BlockSparse:
     def ddts(self, x, s, stream=None):       # x [M, D] -> [D, N]
         out = self._out(x.shape[1], self.cols * 128)
         dmoe_bsmm(OP_DDTS, self.topo, self.rows, self.cols, x.shape[1], x, s, out, stream)
+        return out
+
+    def dds(self, x, s, stream=None):        # x [D, M] -> [D, N]
+        if x.shape[1] != self.rows * 128:
+            raise ValueError("x must have %d columns (got %d)" % (self.rows * 128, x.shape[1]))
+        out = self._out(x.shape[0], self.cols * 128)
+        dmoe_bsmm(OP_DDS, self.topo, self.rows, self.cols, x.shape[0], x, s, out, stream)
         return out
 
 

@@ -57,6 +57,7 @@ struct BsParams {
   int items;               // work items of this launch (weight gradients: may exceed the grid)
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
+  int ka;                  // DDS: leading dimension of dense_a
 };
 
 template <int OP> struct OpLayouts;
@@ -66,6 +67,7 @@ template <> struct OpLayouts<OP_SDDT> { static constexpr int A = KC, B = KC; };
 template <> struct OpLayouts<OP_DSTD> { static constexpr int A = NC, B = NC; };
 template <> struct OpLayouts<OP_DSDT> { static constexpr int A = KC, B = KC; };
 template <> struct OpLayouts<OP_DDTS> { static constexpr int A = NC, B = NC; };
+template <> struct OpLayouts<OP_DDS>  { static constexpr int A = KC, B = NC; };
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup w runs on XCD w % 8).  Work items are cut into
 // patches of P consecutive items that share operands; patch p goes to XCD p % 8, so the items of a patch run
@@ -126,8 +128,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   const size_t ldw = (size_t)p.E * p.h;             // leading dimension of W1 / dW1
   // Which dimension the A panels and the B panels span: rows x block-columns (SDD, SDD^T), rows x d-blocks (DSD,
   // DSD^T), block-columns x d-blocks (DS^TD), d-blocks x block-columns (DD^TS).
-  constexpr int UC = (kSparseOut || OP == OP_DDTS) ? PB : PA;   // block-columns per unit (where columns matter)
-  constexpr int UD = OP == OP_DDTS ? PA : PB;                   // d-blocks per unit
+  constexpr bool kColsInB = OP == OP_DDTS || OP == OP_DDS;      // dense x sparse: the block-columns are the B panels
+  constexpr int UC = (kSparseOut || kColsInB) ? PB : PA;        // block-columns per unit (where columns matter)
+  constexpr int UD = kColsInB ? PA : PB;                        // d-blocks per unit
   const int ncu = (hb + UC - 1) / UC, nju = (db + UD - 1) / UD;
 
   // One workgroup, one tile for the products whose rows are tokens.  The weight-gradient launches are capped at
@@ -215,6 +218,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   else if constexpr (OP == OP_DSD)  { lda = kBlock; ldb = d; }
   else if constexpr (OP == OP_DSDT) { lda = kBlock; ldb = (uint32_t)ldw; }
   else if constexpr (OP == OP_DSTD) { lda = kBlock; ldb = d; }
+  else if constexpr (OP == OP_DDS)  { lda = (uint32_t)p.ka;  ldb = kBlock; }
   else                              { lda = d;      ldb = kBlock; }
 
   // The K loop of the products that walk the topology needs one to three index values per sparse block.  They are
@@ -227,7 +231,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     if (lane < n) {
       if constexpr (OP == OP_DSD || OP == OP_DSDT) {
         ix0 = p.column_indices[first0 + kb0 + lane];
-      } else if constexpr (OP == OP_DSTD || OP == OP_DDTS) {
+      } else if constexpr (OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS) {
         ix0 = p.block_offsets_t[first0 + kb0 + lane];
         ix1 = p.block_offsets_t[first1 + kb0 + lane];
         ix2 = p.row_indices_t[first0 + kb0 + lane];
@@ -273,6 +277,16 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
       b0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
       b1 = b0 + (b_ok[1] ? kBlock : 0);
+    } else if constexpr (OP == OP_DDS) {
+      // Y = X S: for the blocks (row, c) of column c, in the order of the transposed lists, X[:, row] times the block
+      const int i = kt / kSub, half = kt % kSub;
+      if ((kt & (64 * kSub - 1)) == 0) refill(i);
+      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
+      a0 = p.dense_a + (size_t)jd0 * kBlock * p.ka + (size_t)row * kBlock + half * BK;
+      a1 = a0 + (a_ok[1] ? (size_t)kBlock * p.ka : 0);
+      b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
+      b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
     } else {  // OP_DDTS
       const int i = kt / kSub, half = kt % kSub;
       if ((kt & (64 * kSub - 1)) == 0) refill(i);
@@ -543,7 +557,7 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
   int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
   BsParams q = p;
   q.items = grid;
-  constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS;
+  constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS;
   if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
   hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK>), dim3(grid), dim3(NW * 64), kLds, s, q);
 }
@@ -595,11 +609,12 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   p.plain = a.plain;
   p.accum = a.accum;
+  p.ka = a.ka;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless
   // the routing is even enough for patches (sched[1], decided on the device).
-  p.patch = (op == OP_DSTD || op == OP_DDTS) ? 1 : -kPatchSlack;
+  p.patch = (op == OP_DSTD || op == OP_DDTS || op == OP_DDS) ? 1 : -kPatchSlack;
   switch (op) {
     case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;
     case OP_SDDT: launch_one<OP_SDDT>(p, a, s); break;
@@ -607,6 +622,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
     case OP_DSDT: launch_one<OP_DSDT>(p, a, s); break;
     case OP_DSTD: launch_one<OP_DSTD>(p, a, s); break;
     case OP_DDTS: launch_one<OP_DDTS>(p, a, s); break;
+    case OP_DDS:  launch_one<OP_DDS>(p, a, s); break;
   }
 }
 

@@ -133,11 +133,12 @@ int dmoe_bsmm_topology(const uint8_t* mask, int block_rows, int block_cols, void
 
 int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_cols, int dense, const void* a,
               const void* b, void* out, void* stream) {
-  if (op < DMOE_OP_SDD || op > DMOE_OP_DDTS) return fail(DMOE_EINVAL, "unknown product %d", op);
+  if (op < DMOE_OP_SDD || op > DMOE_OP_DDS) return fail(DMOE_EINVAL, "unknown product %d", op);
   if (!topo || !topo->row_offsets || !topo->counts) return fail(DMOE_EINVAL, "topology is NULL or not built");
   if (int rc = check_mask_dims(block_rows, block_cols, 0)) return rc;
   if (dense < kBlock || dense % kBlock) return fail(DMOE_EINVAL, "dense must be a positive multiple of 128 (got %d)", dense);
-  if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32))
+  if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32) ||
+      (long long)block_rows * kBlock * kBlock >= (1ll << 32))
     return fail(DMOE_EINVAL, "operands too large");
   if (int rc = check_ptr(a, "a")) return rc;
   if (int rc = check_ptr(b, "b")) return rc;
@@ -155,6 +156,7 @@ int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_col
     case DMOE_OP_DSTD: g.sparse_in = pa;  g.dense_a = pb;  break;    // Y = S^T X
     case DMOE_OP_DSDT: g.sparse_in = pa;  g.dense_b = pb;  break;    // Y = S W^T
     case DMOE_OP_DDTS: g.dense_a = pa;  g.sparse_in = pb;  break;    // Y = X^T S
+    case DMOE_OP_DDS:  g.dense_a = pa;  g.sparse_in = pb;  g.ka = block_rows * kBlock;  break;   // Y = X S
   }
   (void)hipGetLastError();
   launch_bsmm(static_cast<BsOp>(op), g, static_cast<hipStream_t>(stream));

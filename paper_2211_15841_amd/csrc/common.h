@@ -73,7 +73,7 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
                        bf16_t* dx, float* dw_router, bool accumulate, hipStream_t s);
 int router_bwd_num_partials(const dmoe_config& c);
 
-enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5 };
+enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5, OP_DDS = 6 };
 struct BsArgs {
   const dmoe_topology_t* topo;
   int d, h, E;
@@ -82,6 +82,7 @@ struct BsArgs {
   int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
   int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
   int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
+  int ka;                  // DDS only: leading dimension of dense_a (= 128 * block rows of S)
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))

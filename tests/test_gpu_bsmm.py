@@ -69,6 +69,8 @@ def test_six_products_on_a_mask(name, dense):
     _close(_host(bs.dsdt(sd, wdn_d)), bo.dsdt(s, wdn, mask), "DSD^T")
     _close(_host(bs.dstd(sd, xd)), bo.dstd(s, x, mask), "DS^TD")
     _close(_host(bs.ddts(xd, sd)), bo.ddts(x, s, mask), "DD^TS")
+    xtb, xt = _bf16(rng, (D, M))
+    _close(_host(bs.dds(_dev(xtb), sd)), bo.dds(xt, s, mask), "DDS")
 
     # rows / columns without blocks must come out as exact zeros
     y = _host(bs.dsd(sd, wnd_d))
@@ -77,6 +79,9 @@ def test_six_products_on_a_mask(name, dense):
     z = _host(bs.dstd(sd, xd))
     for c in np.nonzero(~mask.any(axis=0))[0]:
         assert not z[c * 128:(c + 1) * 128].any()
+    v = _host(bs.dds(_dev(xtb), sd))
+    for c in np.nonzero(~mask.any(axis=0))[0]:
+        assert not v[:, c * 128:(c + 1) * 128].any()
 
 
 def test_topology_of_a_mask_is_bit_exact():

@@ -44,6 +44,8 @@ def test_dense_output_products_match_scipy(seed, R, C, density):
     np.testing.assert_allclose(dense @ w_dn.T, S @ w_dn.T, rtol=1e-12, atol=1e-12)             # DSD^T
     np.testing.assert_allclose(dense.T @ x, S.T.tocsr() @ x, rtol=1e-12, atol=1e-12)           # DS^TD
     np.testing.assert_allclose(x.T @ dense, (S.T.tocsr() @ x).T, rtol=1e-12, atol=1e-12)       # DD^TS
+    xt = rng.standard_normal((24, R * B))
+    np.testing.assert_allclose(xt @ dense, (S.T.tocsr() @ xt.T).T, rtol=1e-12, atol=1e-12)     # DDS
 
 
 def test_sample_is_the_inverse_of_densify_on_the_mask():
@@ -69,6 +71,7 @@ def test_full_block_size_functions_on_all_ones_and_empty_masks():
     np.testing.assert_allclose(bo.dsdt(s, w, ones), (x @ w) @ w.T, rtol=1e-10, atol=1e-9)
     np.testing.assert_allclose(bo.dstd(s, x, ones), (x @ w).T @ x, rtol=1e-10, atol=1e-9)
     np.testing.assert_allclose(bo.ddts(x, s, ones), x.T @ (x @ w), rtol=1e-10, atol=1e-9)
+    np.testing.assert_allclose(bo.dds(x.T.copy(), s, ones), x.T @ (x @ w), rtol=1e-10, atol=1e-9)
     zero = np.zeros((R, C), dtype=np.uint8)
     assert bo.sdd(x, w, zero).shape == (0, 128, 128)
     assert not bo.dsd(np.zeros((0, 128, 128)), w.T.copy(), zero).any()
@@ -91,3 +94,20 @@ def test_adjoint_identities_between_the_products():
     lhs = float((bo.sddt(x, w2, mask) * s).sum())
     np.testing.assert_allclose(lhs, float((x * bo.dsd(s, w2, mask)).sum()), rtol=1e-10)
     np.testing.assert_allclose(lhs, float((w2 * bo.dstd(s, x, mask)).sum()), rtol=1e-10)
+
+
+def test_dds_is_the_transpose_of_a_sparse_times_dense_product_and_the_adjoint_of_sdd():
+    """Y = X S has two independent characterisations: Y^T = S^T X^T (the DS^TD product of the transposed input), and
+    <X S, G> = <S, X^T G restricted to the mask> (DDS is what the backward pass of an SDD with a transposed left
+    input would need)."""
+    rng = np.random.default_rng(51)
+    mask = np.array([[1, 0, 1], [0, 0, 1], [1, 1, 0], [0, 0, 0]], dtype=np.uint8)
+    R, C, D = mask.shape[0], mask.shape[1], 128
+    x = rng.standard_normal((D, R * 128))
+    s = rng.standard_normal((int(mask.sum()), 128, 128))
+    y = bo.dds(x, s, mask)
+    np.testing.assert_allclose(y, bo.dstd(s, x.T.copy(), mask).T, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(y, bo.ddts(x.T.copy(), s, mask), rtol=1e-12, atol=1e-12)
+    g = rng.standard_normal((D, C * 128))
+    np.testing.assert_allclose(float((y * g).sum()), float((s * bo.sdd(x.T.copy(), g, mask)).sum()), rtol=1e-10)
+    assert y.shape == (D, C * 128)
