@@ -32,14 +32,14 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "sdd"): 279892173, ("xs", "dsd"): 217564774, ("xs", "sddt"): 279845683,
-    ("xs", "dstd"): 196621107, ("xs", "dsdt"): 217561907, ("xs", "ddts"): 196636262,
-    ("small_zipf1.0", "sdd"): 638837965, ("small_zipf1.0", "dsd"): 542679859, ("small_zipf1.0", "sddt"): 638236058,
-    ("small_zipf1.0", "dstd"): 980830003, ("small_zipf1.0", "dsdt"): 542817485, ("small_zipf1.0", "ddts"): 981277491,
-    ("medium_zipf1.2_top2", "sdd"): 2360531149, ("medium_zipf1.2_top2", "dsd"): 2597010432, ("medium_zipf1.2_top2", "sddt"): 2363080090,
-    ("medium_zipf1.2_top2", "dstd"): 2839578419, ("medium_zipf1.2_top2", "dsdt"): 2618286285, ("medium_zipf1.2_top2", "ddts"): 2875448934,
-    ("large_expert_top2", "sdd"): 16602969498, ("large_expert_top2", "dsd"): 14576305152, ("large_expert_top2", "sddt"): 18105627034,
-    ("large_expert_top2", "dstd"): 13386441933, ("large_expert_top2", "dsdt"): 15569899315, ("large_expert_top2", "ddts"): 22778809549,
+    ("xs", "sdd"): 279949312, ("xs", "dsd"): 218877338, ("xs", "sddt"): 279871693,
+    ("xs", "dstd"): 193072230, ("xs", "dsdt"): 217856000, ("xs", "ddts"): 193143910,
+    ("small_zipf1.0", "sdd"): 638781440, ("small_zipf1.0", "dsd"): 543215411, ("small_zipf1.0", "sddt"): 638287872,
+    ("small_zipf1.0", "dstd"): 1007989146, ("small_zipf1.0", "dsdt"): 542797005, ("small_zipf1.0", "ddts"): 984878490,
+    ("medium_zipf1.2_top2", "sdd"): 2359126630, ("medium_zipf1.2_top2", "dsd"): 2590814003, ("medium_zipf1.2_top2", "sddt"): 2365401702,
+    ("medium_zipf1.2_top2", "dstd"): 2813959578, ("medium_zipf1.2_top2", "dsdt"): 2616198758, ("medium_zipf1.2_top2", "ddts"): 2814806528,
+    ("large_expert_top2", "sdd"): 17414645350, ("large_expert_top2", "dsd"): 13780411187, ("large_expert_top2", "sddt"): 18134873498,
+    ("large_expert_top2", "dstd"): 13422674125, ("large_expert_top2", "dsdt"): 15500668109, ("large_expert_top2", "ddts"): 13380331520,
 }
 
 
