@@ -58,7 +58,8 @@ typedef struct {
   int32_t num_experts;     /* E */
   int32_t top_k;           /* k  experts per token (Section 2.1) */
   int32_t block;           /* must be 128 */
-  int32_t activation;      /* 0: exact GELU  v*Phi(v)  between the two expert layers */
+  int32_t activation;      /* between the two expert layers: 0 exact GELU v*Phi(v); 1 its tanh form
+                              0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))) */
   int32_t normalize_topk;  /* 0: confidence = softmax probability of the chosen expert (Section 2.1);
                               1: that, divided by the sum over the token's k chosen experts */
 } dmoe_config;

@@ -60,6 +60,27 @@ def gelu_grad(v: np.ndarray) -> np.ndarray:
     return 0.5 * (1.0 + _erf(v / math.sqrt(2.0))) + v * np.exp(-0.5 * v * v) / math.sqrt(2.0 * math.pi)
 
 
+def gelu_tanh(v: np.ndarray) -> np.ndarray:
+    """The tanh form of GELU:  0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))  (activation = 1)."""
+    return 0.5 * v * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3)))
+
+
+def gelu_tanh_grad(v: np.ndarray) -> np.ndarray:
+    """Derivative of the tanh form: with u = sqrt(2/pi)(v + 0.044715 v^3) and t = tanh u,
+    0.5 (1 + t) + 0.5 v (1 - t^2) sqrt(2/pi) (1 + 3 * 0.044715 v^2)."""
+    t = np.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3))
+    return 0.5 * (1.0 + t) + 0.5 * v * (1.0 - t * t) * math.sqrt(2.0 / math.pi) * (1.0 + 3.0 * 0.044715 * v * v)
+
+
+def activation_pair(activation: int):
+    """(act, act') for the configuration's `activation` field: 0 exact GELU, 1 tanh form."""
+    if activation == 0:
+        return gelu, gelu_grad
+    if activation == 1:
+        return gelu_tanh, gelu_tanh_grad
+    raise ValueError("activation must be 0 or 1")
+
+
 # ----------------------------------------------------------------------------- router (Section 2.1)
 def router_logits(x_bits: np.ndarray, wr_bits: np.ndarray, bias: np.ndarray | None) -> np.ndarray:
     """float32 scores[t,e] = sum_i x[t,i] * Wr[i,e], accumulated for i = 0, 1, ... in that order
@@ -226,7 +247,7 @@ def _members(expert_idx: np.ndarray, e: int) -> np.ndarray:
     return np.flatnonzero(np.asarray(expert_idx).reshape(-1) == e)
 
 
-def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep: bool = False):
+def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep: bool = False, activation: int = 0):
     """y[t] = sum_s weights[t,s] * FFN_{e(t,s)}(x[t]),  FFN_e(v) = gelu(v W1_e) W2_e   (Sections 2.3-2.4, Fig. 6).
 
     Returns y float64 [T,d]; with keep=True also the per-expert intermediates for backward()."""
@@ -247,7 +268,7 @@ def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep
         W2_e = widen_bf16(w2_bits[e * h:(e + 1) * h, :])
         X_e = x[tok]
         H_e = X_e @ W1_e
-        A_e = gelu(H_e)
+        A_e = activation_pair(activation)[0](H_e)
         O_e = A_e @ W2_e
         np.add.at(y, tok, w_flat[S_e, None] * O_e)
         if keep:
@@ -256,7 +277,7 @@ def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep
 
 
 def backward(x_bits, wr_bits, w1_bits, w2_bits, dy_bits, expert_idx, weights, probs, ffn_hidden: int,
-             normalize_topk: int):
+             normalize_topk: int, activation: int = 0):
     """Gradients of  L = <dy, y>  with the expert assignments held constant.
 
     Returns dx [T,d], dw_router [d,E], dw1 [d,E*h], dw2 [E*h,d] (float64), and dweights [T,k]."""
@@ -268,7 +289,7 @@ def backward(x_bits, wr_bits, w1_bits, w2_bits, dy_bits, expert_idx, weights, pr
     wr = widen_bf16(wr_bits)
     dy = widen_bf16(dy_bits)
     w_flat = np.asarray(weights, dtype=np.float64).reshape(-1)
-    _, saved = forward(x_bits, w1_bits, w2_bits, expert_idx, weights, h, keep=True)
+    _, saved = forward(x_bits, w1_bits, w2_bits, expert_idx, weights, h, keep=True, activation=activation)
 
     dx = np.zeros((T, d))
     dw1 = np.zeros((d, E * h))
@@ -285,7 +306,7 @@ def backward(x_bits, wr_bits, w1_bits, w2_bits, dy_bits, expert_idx, weights, pr
         dwt[S_e] = np.einsum("ij,ij->i", dy[tok], O_e)
         dw2[e * h:(e + 1) * h, :] = A_e.T @ dO_e
         dA_e = dO_e @ W2_e.T
-        dH_e = dA_e * gelu_grad(H_e)
+        dH_e = dA_e * activation_pair(activation)[1](H_e)
         dw1[:, e * h:(e + 1) * h] = X_e.T @ dH_e
         np.add.at(dx, tok, dH_e @ W1_e.T)
 

@@ -246,8 +246,9 @@ def dmoe_set_stage_events(events_array):
 class Workspace:
     """Caller-side buffers for one layer configuration, allocated once with torch (device memory only)."""
 
-    def __init__(self, num_tokens, d_model, ffn_hidden, num_experts, top_k, normalize_topk=0, device="cuda:0"):
-        self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, 0, normalize_topk)
+    def __init__(self, num_tokens, d_model, ffn_hidden, num_experts, top_k, normalize_topk=0, device="cuda:0",
+                 activation=0):
+        self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, activation, normalize_topk)
         self.device = torch.device(device)
         self.sizes = dmoe_sizes(self.cfg)
         u8 = dict(dtype=torch.uint8, device=self.device)

@@ -35,7 +35,7 @@ static int check_config(const dmoe_config* c, Dims* out) {
   if (c->ffn_hidden < kBlock || c->ffn_hidden % kBlock) return fail(DMOE_EINVAL, "ffn_hidden must be a positive multiple of 128 (got %d)", c->ffn_hidden);
   if (c->num_experts < 1 || c->num_experts > kMaxExperts) return fail(DMOE_EINVAL, "num_experts must be in [1, %d] (got %d)", kMaxExperts, c->num_experts);
   if (c->top_k < 1 || c->top_k > kMaxTopK || c->top_k > c->num_experts) return fail(DMOE_EINVAL, "top_k must be in [1, min(num_experts, %d)] (got %d)", kMaxTopK, c->top_k);
-  if (c->activation != 0) return fail(DMOE_EINVAL, "activation must be 0 (exact GELU)");
+  if (c->activation != 0 && c->activation != 1) return fail(DMOE_EINVAL, "activation must be 0 (exact GELU) or 1 (tanh form)");
   if (c->normalize_topk != 0 && c->normalize_topk != 1) return fail(DMOE_EINVAL, "normalize_topk must be 0 or 1");
   const long long F = (long long)c->num_tokens * c->top_k;
   if (F >= (1ll << 24)) return fail(DMOE_EINVAL, "num_tokens*top_k must be below 2^24 (got %lld)", F);
@@ -236,6 +236,7 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
   a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
   ev.begin(DMOE_STAGE_SDD);
   a.dense_a = xp; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = nullptr; a.out0 = hval; a.out1 = aval;
+  a.act = cfg->activation;
   launch_bsmm(OP_SDD, a, s);
   ev.end(DMOE_STAGE_SDD);
 

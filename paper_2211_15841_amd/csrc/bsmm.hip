@@ -58,6 +58,7 @@ struct BsParams {
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
   int ka;                  // DDS: leading dimension of dense_a
+  int act;                 // SDD epilogue: 0 exact GELU, 1 tanh form
 };
 
 template <int OP> struct OpLayouts;
@@ -503,7 +504,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             float c, d0;
-            normal_cdf_pdf(v[u], c, d0);
+            if (p.act) tanh_gelu_cdf_pdf(v[u], c, d0);
+            else       normal_cdf_pdf(v[u], c, d0);
             g[u] = fmaf(v[u], d0, c);
             v[u] *= c;
             acc[i][jj][4 * q + u] = v[u];          // keep A for the second pass through the staging tile
@@ -610,6 +612,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.plain = a.plain;
   p.accum = a.accum;
   p.ka = a.ka;
+  p.act = a.act;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless

@@ -47,6 +47,15 @@ __device__ __forceinline__ void normal_cdf_pdf(float v, float& cdf, float& pdf) 
   cdf = v < 0.0f ? tail : 1.0f - tail;
   pdf = ex * 0.39894228040143268f;
 }
+// The tanh form of GELU, 0.5 v (1 + tanh(u)) with u = sqrt(2/pi) (v + 0.044715 v^3), written the same way: `cdf` is
+// the factor that multiplies v (0.5 (1 + tanh u) = 1 / (1 + exp(-2u))) and `pdf` the factor of v in the derivative,
+// d/dv = cdf + v * pdf with pdf = 0.5 (1 - tanh^2 u) u' = 2 cdf (1 - cdf) u'.
+__device__ __forceinline__ void tanh_gelu_cdf_pdf(float v, float& cdf, float& pdf) {
+  const float v2 = v * v;
+  const float u = 0.79788456080286536f * v * fmaf(0.044715f, v2, 1.0f);
+  cdf = __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));           // exp overflow -> rcp(inf) = 0, as it should be
+  pdf = 2.0f * cdf * (1.0f - cdf) * 0.79788456080286536f * fmaf(0.134145f, v2, 1.0f);
+}
 struct StageEvents {            // optional per-stage timing events (see dmoe_set_stage_events)
   hipEvent_t* ev;
   hipStream_t stream;
@@ -83,6 +92,7 @@ struct BsArgs {
   int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
   int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
   int ka;                  // DDS only: leading dimension of dense_a (= 128 * block rows of S)
+  int act;                 // SDD's fused activation: 0 exact (erf) GELU, 1 tanh form
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))

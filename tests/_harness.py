@@ -22,7 +22,8 @@ def bf16_to_np(t: torch.Tensor) -> np.ndarray:
 
 
 def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
-    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk)
+    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk,
+                      activation=cfg.activation)
     if poison:      # unwritten regions must not look like zeros (empty experts, padding rows)
         for t in (ws.topology_mem, ws.saved, ws.scratch):
             t.fill_(0xFF)
@@ -114,9 +115,9 @@ def full_parity(cfg: Config, inp: dict | None = None):
     ref = run_oracle_indices(cfg, inp)
     check_indices(gpu["topo"], ref)
     h = cfg.ffn_hidden
-    y = orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], h)
+    y = orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], h, activation=cfg.activation)
     g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], ref["expert_idx"], ref["weights"],
-                     ref["probs"], h, cfg.normalize_topk)
+                     ref["probs"], h, cfg.normalize_topk, activation=cfg.activation)
     errs = {"y": check_values("y", gpu["y"], y)}
     for name in ("dx", "dw1", "dw2"):
         errs[name] = check_values(name, gpu[name], g[name])

@@ -40,7 +40,7 @@ def test_sizes_follow_the_documented_bounds():
 @pytest.mark.parametrize("kw,frag", [
     (dict(block=64), "block"), (dict(d=200), "d_model"), (dict(h=100), "ffn_hidden"), (dict(E=0), "num_experts"),
     (dict(E=257), "num_experts"), (dict(k=0), "top_k"), (dict(k=5, E=4), "top_k"), (dict(k=9, E=16), "top_k"),
-    (dict(T=0), "num_tokens"), (dict(act=1), "activation"), (dict(norm=2), "normalize_topk"),
+    (dict(T=0), "num_tokens"), (dict(act=2), "activation"), (dict(norm=2), "normalize_topk"),
 ])
 def test_invalid_configurations_are_rejected(kw, frag):
     with pytest.raises(dm.DMoEError) as ei:

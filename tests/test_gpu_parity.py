@@ -103,3 +103,36 @@ def test_both_tile_shapes_give_the_same_answers(mode):
             full_parity(cfg)
     finally:
         dm.dmoe_set_tile_mode(0)
+
+
+@pytest.mark.parametrize("tile_mode", [1, 2], ids=["tiles_128", "tiles_256"])
+def test_tanh_form_of_the_activation(tile_mode):
+    """activation = 1: the fused epilogue of SDD (activation and its derivative) in the tanh form.
+
+    The two forms differ by at most 5e-4 in absolute value, far inside the 1e-2 tolerance, so parity alone could
+    not tell which one the kernel evaluates.  The difference is systematic, though, while bf16 rounding is not:
+    the projection of (y_gpu - y_exact) on (y_tanh - y_exact), both from the oracle, is 1 if the kernel uses the tanh
+    form and 0 if it uses the exact one, give or take about 0.06 of rounding noise at this size."""
+    import dataclasses
+    import paper_2211_15841_amd as dm
+    from dmoe_inputs import bf16_bits_to_f32
+    from oracle import dmoe_oracle as orc
+    base = small_config("tanh_k2", T=2000, d=256, h=384, E=6, k=2, normalize_topk=1, seed=131)
+    inp = make_inputs(base)
+    # scale the first layer up so that the pre-activations reach |v| ~ 2, where the two forms differ most
+    inp["w1"] = f32_to_bf16_bits(bf16_bits_to_f32(np.asarray(inp["w1"]).view(np.uint16)) * 6.0)
+    dm.dmoe_set_tile_mode(tile_mode)
+    try:
+        proj = {}
+        for act in (1, 0):
+            cfg = dataclasses.replace(base, activation=act)
+            errs, gpu, ref = full_parity(cfg, inp)
+            y = {a: orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], cfg.ffn_hidden,
+                                activation=a) for a in (0, 1)}
+            delta = y[1] - y[0]
+            proj[act] = float(((gpu["y"] - y[0]) * delta).sum() / (delta * delta).sum())
+            print("activation", act, errs, "projection on the form difference %.3f" % proj[act])
+        assert proj[1] > 0.7, proj
+        assert proj[0] < 0.3, proj
+    finally:
+        dm.dmoe_set_tile_mode(0)

@@ -28,7 +28,11 @@ MUTATIONS = {
     "forward_uses_wrong_expert_slice_of_w2": ("W2_e = widen_bf16(w2_bits[e * h:(e + 1) * h, :])\n        X_e = x[tok]",
                                               "W2_e = widen_bf16(w2_bits[0:h, :])\n        X_e = x[tok]"),
     "dw2_from_preactivation": ("dw2[e * h:(e + 1) * h, :] = A_e.T @ dO_e", "dw2[e * h:(e + 1) * h, :] = H_e.T @ dO_e"),
-    "dw1_without_activation_derivative": ("dH_e = dA_e * gelu_grad(H_e)", "dH_e = dA_e"),
+    "dw1_without_activation_derivative": ("dH_e = dA_e * activation_pair(activation)[1](H_e)", "dH_e = dA_e"),
+    "tanh_gelu_wrong_cubic_coefficient": ("return 0.5 * v * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3)))",
+                                          "return 0.5 * v * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (v + 0.44715 * v ** 3)))"),
+    "tanh_gelu_grad_forgets_inner_derivative": (" * (1.0 + 3.0 * 0.044715 * v * v)", ""),
+    "backward_uses_exact_derivative_for_tanh_form": ("dH_e = dA_e * activation_pair(activation)[1](H_e)", "dH_e = dA_e * gelu_grad(H_e)"),
     "dx_forgets_router_term": ("dx += dlogits @ wr.T", "pass"),
     "dweights_sign": ("dwt[S_e] = np.einsum(\"ij,ij->i\", dy[tok], O_e)", "dwt[S_e] = -np.einsum(\"ij,ij->i\", dy[tok], O_e)"),
     "renormalisation_gradient_drops_mean": ("dsel = (dwt - (dwt * w).sum(axis=1, keepdims=True)) / Z", "dsel = dwt / Z"),
@@ -51,6 +55,8 @@ def _pins():
         lambda: tv.test_forward_equals_dense_masked_brute_force(tv.CASES[1]),
         lambda: tv.test_single_expert_is_the_textbook_mlp(),
         lambda: tv.test_gelu_values_and_derivative(),
+        lambda: tv.test_tanh_gelu_values_and_derivative(),
+        lambda: tv.test_tanh_form_forward_and_backward_equal_torch_autograd(),
         lambda: tv.test_backward_equals_torch_autograd_on_dense_formulation(tv.CASES[1]),
         lambda: tv.test_backward_equals_torch_autograd_on_dense_formulation(tv.CASES[2]),
         lambda: tv.test_top1_with_normalised_weight_gives_router_no_gradient(),

@@ -109,7 +109,7 @@ def test_gelu_values_and_derivative():
 
 
 # ----------------------------------------------------------------------------- gradients
-def _torch_dense(cfg, inp, idx):
+def _torch_dense(cfg, inp, idx, activation=0):
     """Differentiable dense masked formulation in torch float64 (routing indices held constant)."""
     E, h = cfg.num_experts, cfg.ffn_hidden
     leaves = {k: torch.tensor(_f64(inp[k]), requires_grad=True) for k in ("x", "w_router", "w1", "w2")}
@@ -125,7 +125,8 @@ def _torch_dense(cfg, inp, idx):
     G = torch.zeros_like(p).scatter(1, ti, sel)
     y = 0
     for e in range(E):
-        y = y + G[:, e:e + 1] * (torch.nn.functional.gelu(x @ w1[:, e * h:(e + 1) * h]) @ w2[e * h:(e + 1) * h, :])
+        hid = torch.nn.functional.gelu(x @ w1[:, e * h:(e + 1) * h], approximate="tanh" if activation else "none")
+        y = y + G[:, e:e + 1] * (hid @ w2[e * h:(e + 1) * h, :])
     return leaves, y, sel
 
 
@@ -251,3 +252,42 @@ def test_weight_gradients_add_up_over_micro_batches():
         assert np.abs(gj[k]).max() > 0
         assert np.allclose(ga[k] + gb[k], gj[k], rtol=1e-10, atol=1e-12 * np.abs(gj[k]).max()), k
     assert np.allclose(np.concatenate([ga["dx"], gb["dx"]]), gj["dx"], rtol=1e-10, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- the tanh form (activation = 1)
+def test_tanh_gelu_values_and_derivative():
+    """The tanh form against torch's own (an independent library routine), its limits, its distance from the exact
+    form (close, but not the same function), and its derivative against central differences."""
+    v = np.linspace(-8, 8, 321)
+    ref = torch.nn.functional.gelu(torch.tensor(v), approximate="tanh").numpy()
+    assert np.allclose(orc.gelu_tanh(v), ref, rtol=1e-13, atol=1e-15)
+    assert orc.gelu_tanh(np.array([0.0]))[0] == 0.0 and orc.gelu_tanh_grad(np.array([0.0]))[0] == 0.5
+    big = np.array([12.0, 30.0])
+    assert np.allclose(orc.gelu_tanh(big), big) and np.allclose(orc.gelu_tanh_grad(big), 1.0)
+    assert np.all(np.abs(orc.gelu_tanh(-big)) < 1e-30) and np.all(np.abs(orc.gelu_tanh_grad(-big)) < 1e-30)
+    gap = np.abs(orc.gelu_tanh(v) - orc.gelu(v)).max()
+    assert 1e-4 < gap < 1e-3
+    eps = 1e-6
+    fd = (orc.gelu_tanh(v + eps) - orc.gelu_tanh(v - eps)) / (2 * eps)
+    assert np.allclose(orc.gelu_tanh_grad(v), fd, rtol=1e-8, atol=1e-9)
+    assert orc.activation_pair(0) == (orc.gelu, orc.gelu_grad) and orc.activation_pair(1) == (orc.gelu_tanh, orc.gelu_tanh_grad)
+    with pytest.raises(ValueError):
+        orc.activation_pair(2)
+
+
+def test_tanh_form_forward_and_backward_equal_torch_autograd():
+    cfg = CASES[1]
+    inp = make_inputs(cfg)
+    logits, idx, w, p = _route(cfg, inp)
+    y = orc.forward(inp["x"], inp["w1"], inp["w2"], idx, w, cfg.ffn_hidden, activation=1)
+    g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], idx, w, p, cfg.ffn_hidden,
+                     cfg.normalize_topk, activation=1)
+    leaves, yt, sel = _torch_dense(cfg, inp, idx, activation=1)
+    yt.backward(torch.tensor(_f64(inp["dy"])))
+    assert np.abs(y - yt.detach().numpy()).max() <= 2e-5 * np.abs(y).max()
+    for name, leaf in (("dx", "x"), ("dw_router", "w_router"), ("dw1", "w1"), ("dw2", "w2")):
+        ref = leaves[leaf].grad.numpy()
+        assert np.abs(g[name] - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-12, name
+    # and it is not the exact form in disguise
+    y0 = orc.forward(inp["x"], inp["w1"], inp["w2"], idx, w, cfg.ffn_hidden)
+    assert np.abs(y - y0).max() > 1e-7 * np.abs(y0).max()
