@@ -58,7 +58,6 @@ struct BsParams {
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
   int ka;                  // DDS: leading dimension of dense_a
-  int act;                 // SDD epilogue: 0 exact GELU, 1 tanh form
 };
 
 template <int OP> struct OpLayouts;
@@ -101,7 +100,7 @@ __device__ __forceinline__ int balanced_patch(int items, int slack) {
 //   2,1 -> 256x128 (each wave 64x64), three LDS stages;
 //   1,1 -> a single 128x128 block shared by eight waves (32x64 each), two or more workgroups per CU: half the
 //          arithmetic intensity but four times as many work items, for under-filled launches.
-template <int OP, int PA, int PB, int NS, int NW, int BK = 64>
+template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
 __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
   constexpr int kSub = kBlock / BK;                 // K tiles per 128-wide sparse block
@@ -451,7 +450,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
             v.z = acc[i][jj][4 * q + 2];  v.w = acc[i][jj][4 * q + 3];
             *reinterpret_cast<float4*>(ep + kc_offset<64>(32 * i + (lane & 31), 2 * q + (lane >> 5))) = v;
           }
-#pragma unroll
+#pragma unroll 2                               // not fully: the hoisted addresses would cost registers in every variant
         for (int it = 0; it < 4 * MI; ++it) {
           const int row = 8 * it + (lane >> 3), chunk = lane & 7;
           const float4 v = *reinterpret_cast<const float4*>(ep + kc_offset<64>(row, chunk));
@@ -487,6 +486,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // SDD writes two tensors from the same fp32 values: out1 <- A = gelu(H) = H Phi(H) for the second layer, and
   // out0 <- G = gelu'(H) = Phi(H) + H phi(H), which is all the backward pass needs of H (one evaluation of Phi and
   // phi serves both, and SDD^T then only multiplies).
+  // (The form of the activation, ACT, is a template parameter: a run-time choice inside this loop made the compiler
+  // evaluate both forms for every element, and one copy of the loop per form cost the 256x256 tile its registers.)
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -504,8 +505,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             float c, d0;
-            if (p.act) tanh_gelu_cdf_pdf(v[u], c, d0);
-            else       normal_cdf_pdf(v[u], c, d0);
+            if constexpr (ACT == 1) tanh_gelu_cdf_pdf(v[u], c, d0);
+            else                    normal_cdf_pdf(v[u], c, d0);
             g[u] = fmaf(v[u], d0, c);
             v[u] *= c;
             acc[i][jj][4 * q + u] = v[u];          // keep A for the second pass through the staging tile
@@ -546,12 +547,12 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   }
 }
 
-template <int OP, int PA, int PB, int NS, int NW, int BK = 64>
+template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
 static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
   static bool configured = false;
   constexpr int kLds = NS * (PA + PB) * 256 * BK;
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW, BK>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     configured = true;
   }
@@ -561,7 +562,7 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
   q.items = grid;
   constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS;
   if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
-  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK>), dim3(grid), dim3(NW * 64), kLds, s, q);
+  hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>), dim3(grid), dim3(NW * 64), kLds, s, q);
 }
 
 // Other shapes the template covers were measured on MI355X and lost: 16 waves of 64x64 on the 256x256 tile (-2..6 %),
@@ -589,6 +590,13 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
     bool small = (long long)a.groups_est * big_minor < 256 + (sparse_out ? 1 : 0);
     if (a.force_tile == 1) small = true;
     if (a.force_tile == 2) small = false;
+    if constexpr (OP == OP_SDD) {
+      if (a.act == 1 && !a.plain) {               // the tanh form of the activation is its own instantiation
+        if (small) launch_variant<OP, 1, 1, 2, 8, 64, 1>(p, a.r_max, hb, s);
+        else       launch_variant<OP, 2, 2, 2, 8, 64, 1>(p, a.g_max, big_minor, s);
+        return;
+      }
+    }
     if (small) launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
     else       launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
   } else {
@@ -612,7 +620,6 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.plain = a.plain;
   p.accum = a.accum;
   p.ka = a.ka;
-  p.act = a.act;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless
