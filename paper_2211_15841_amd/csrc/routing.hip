@@ -44,31 +44,55 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
   for (int e0 = 0; e0 < E; e0 += EPAD) {
     static_assert(kRouterTPT % 4 == 0, "tokens per lane come in groups of four (one 4x4 block each)");
     f32x4_v acc4[kRouterTPT / 4];
+    constexpr int NX = (TT * (kRouterKT / 8) + 255) / 256;                        // 16-byte loads of x per thread and K tile
+    constexpr int NWV = EPAD >= 8 ? (kRouterKT * (EPAD / 8) + 255) / 256 : 1;     // ... of Wr (vector path)
+    uint4 xr[NX], wv[NWV];
 #pragma unroll
     for (int g = 0; g < kRouterTPT / 4; ++g) acc4[g] = f32x4_v{0.0f, 0.0f, 0.0f, 0.0f};
 
-    for (int i0 = 0; i0 < d; i0 += kRouterKT) {
-      __syncthreads();
-      for (int q = tid; q < TT * (kRouterKT / 8); q += 256) {
-        const int tl = q / (kRouterKT / 8), c = q % (kRouterKT / 8);
-        const int t = tile0 + tl;
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (t < T) raw = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c * 8);
-        float4 lo = make_float4(bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y));
-        float4 hi = make_float4(bf16_lo(raw.z), bf16_hi(raw.z), bf16_lo(raw.w), bf16_hi(raw.w));
-        *reinterpret_cast<float4*>(&xs[tl * XP + c * 8]) = lo;
-        *reinterpret_cast<float4*>(&xs[tl * XP + c * 8 + 4]) = hi;
+    // The raw bf16 of the next K tile is fetched into registers while the current one is multiplied: without that,
+    // every K tile exposes one global-load latency between two barriers.
+    auto fetch = [&](int i0) {
+#pragma unroll
+      for (int u = 0; u < NX; ++u) {
+        const int q = tid + 256 * u;
+        xr[u] = make_uint4(0, 0, 0, 0);
+        if (q < TT * (kRouterKT / 8)) {
+          const int tl = q / (kRouterKT / 8), c = q % (kRouterKT / 8);
+          const int t = tile0 + tl;
+          if (t < T) xr[u] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c * 8);
+        }
       }
       if (vec_w && EPAD >= 8) {
-        for (int q = tid; q < kRouterKT * (EPAD / 8); q += 256) {
-          const int i = q / (EPAD / 8), c = q % (EPAD / 8);
-          const int e = e0 + c * 8;
-          uint4 raw = make_uint4(0, 0, 0, 0);
-          if (e < E) raw = *reinterpret_cast<const uint4*>(wr + (size_t)(i0 + i) * E + e);
-          float4 lo = make_float4(bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y));
-          float4 hi = make_float4(bf16_lo(raw.z), bf16_hi(raw.z), bf16_lo(raw.w), bf16_hi(raw.w));
-          *reinterpret_cast<float4*>(&ws[i * EPAD + c * 8]) = lo;
-          *reinterpret_cast<float4*>(&ws[i * EPAD + c * 8 + 4]) = hi;
+#pragma unroll
+        for (int u = 0; u < NWV; ++u) {
+          const int q = tid + 256 * u;
+          wv[u] = make_uint4(0, 0, 0, 0);
+          if (q < kRouterKT * (EPAD / 8)) {
+            const int i = q / (EPAD / 8), c = q % (EPAD / 8);
+            const int e = e0 + c * 8;
+            if (e < E) wv[u] = *reinterpret_cast<const uint4*>(wr + (size_t)(i0 + i) * E + e);
+          }
+        }
+      }
+    };
+    auto widen_store = [](float* dst, uint4 raw) {
+      *reinterpret_cast<float4*>(dst) = make_float4(bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y));
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(bf16_lo(raw.z), bf16_hi(raw.z), bf16_lo(raw.w), bf16_hi(raw.w));
+    };
+    fetch(0);
+    for (int i0 = 0; i0 < d; i0 += kRouterKT) {
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < NX; ++u) {
+        const int q = tid + 256 * u;
+        if (q < TT * (kRouterKT / 8)) widen_store(&xs[(q / (kRouterKT / 8)) * XP + (q % (kRouterKT / 8)) * 8], xr[u]);
+      }
+      if (vec_w && EPAD >= 8) {
+#pragma unroll
+        for (int u = 0; u < NWV; ++u) {
+          const int q = tid + 256 * u;
+          if (q < kRouterKT * (EPAD / 8)) widen_store(&ws[(q / (EPAD / 8)) * EPAD + (q % (EPAD / 8)) * 8], wv[u]);
         }
       } else {
         for (int q = tid; q < kRouterKT * EPAD; q += 256) {
@@ -77,6 +101,7 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
         }
       }
       __syncthreads();
+      if (i0 + kRouterKT < d) fetch(i0 + kRouterKT);
 #pragma unroll 4
       for (int i = 0; i < kRouterKT; i += 4) {
         const float w0 = ws[(i + 0) * EPAD + el], w1 = ws[(i + 1) * EPAD + el];
