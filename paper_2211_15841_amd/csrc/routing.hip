@@ -63,15 +63,17 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
           if (t < T) xr[u] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + c * 8);
         }
       }
-      if (vec_w && EPAD >= 8) {
+      if constexpr (EPAD >= 8) {
+        if (vec_w) {
 #pragma unroll
-        for (int u = 0; u < NWV; ++u) {
-          const int q = tid + 256 * u;
-          wv[u] = make_uint4(0, 0, 0, 0);
-          if (q < kRouterKT * (EPAD / 8)) {
-            const int i = q / (EPAD / 8), c = q % (EPAD / 8);
-            const int e = e0 + c * 8;
-            if (e < E) wv[u] = *reinterpret_cast<const uint4*>(wr + (size_t)(i0 + i) * E + e);
+          for (int u = 0; u < NWV; ++u) {
+            const int q = tid + 256 * u;
+            wv[u] = make_uint4(0, 0, 0, 0);
+            if (q < kRouterKT * (EPAD / 8)) {
+              const int i = q / (EPAD / 8), c = q % (EPAD / 8);
+              const int e = e0 + c * 8;
+              if (e < E) wv[u] = *reinterpret_cast<const uint4*>(wr + (size_t)(i0 + i) * E + e);
+            }
           }
         }
       }
@@ -88,13 +90,18 @@ __global__ void __launch_bounds__(256) router_logits_kernel(const bf16_t* __rest
         const int q = tid + 256 * u;
         if (q < TT * (kRouterKT / 8)) widen_store(&xs[(q / (kRouterKT / 8)) * XP + (q % (kRouterKT / 8)) * 8], xr[u]);
       }
-      if (vec_w && EPAD >= 8) {
+      bool staged = false;
+      if constexpr (EPAD >= 8) {
+        if (vec_w) {
 #pragma unroll
-        for (int u = 0; u < NWV; ++u) {
-          const int q = tid + 256 * u;
-          if (q < kRouterKT * (EPAD / 8)) widen_store(&ws[(q / (EPAD / 8)) * EPAD + (q % (EPAD / 8)) * 8], wv[u]);
+          for (int u = 0; u < NWV; ++u) {
+            const int q = tid + 256 * u;
+            if (q < kRouterKT * (EPAD / 8)) widen_store(&ws[(q / (EPAD / 8)) * EPAD + (q % (EPAD / 8)) * 8], wv[u]);
+          }
+          staged = true;
         }
-      } else {
+      }
+      if (!staged) {
         for (int q = tid; q < kRouterKT * EPAD; q += 256) {
           const int i = q / EPAD, e = e0 + q % EPAD;
           ws[q] = e < E ? bf16_to_f32(wr[(size_t)(i0 + i) * E + e]) : 0.0f;
