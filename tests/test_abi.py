@@ -110,3 +110,14 @@ def test_general_products_validate_their_arguments():
     assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 100, 256, 256, 256, None) != 0      # dense not a multiple
     assert "multiple of 128" in dm.dmoe_last_error()
     assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 128, None, 256, 256, None) != 0     # NULL operand
+
+
+def test_a_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """There is no CPU or eager fallback: without the built library the binding raises and says how to build it."""
+    from paper_2211_15841_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libdmoe.so"))
+    with pytest.raises(dm.DMoEError, match="not built"):
+        binding.load_library()
+    with pytest.raises(dm.DMoEError, match="not built"):
+        dm.dmoe_sizes(_cfg())
