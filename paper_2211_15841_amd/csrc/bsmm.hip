@@ -359,7 +359,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // the loads behind the arithmetic of the same iteration buys nothing there.  Its two stages are used the other
   // way round: a stage is refilled (with tile kt + 2) as soon as every wave has multiplied it, one barrier later,
   // which keeps two tiles in flight instead of one (-9 % on the weight gradients under skewed routing, -1...4 % on a step).
-  if constexpr (PA * PB == 1 && NS == 2) {
+  if constexpr (PA * PB <= 2 && NS == 2) {
     for (int t = 0; t < 2; ++t) {
       if (t < nk) {
         slab_ptrs(t);
@@ -594,6 +594,15 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
       if (a.act == 1 && !a.plain) {               // the tanh form of the activation is its own instantiation
         if (small) launch_variant<OP, 1, 1, 2, 8, 64, 1>(p, a.r_max, hb, s);
         else       launch_variant<OP, 2, 2, 2, 8, 64, 1>(p, a.g_max, big_minor, s);
+        return;
+      }
+    }
+    if constexpr (OP == OP_DSD) {
+      // 128x256 tiles for DSD when the rows are few but the output is wide enough for every other CU to get one: the
+      // block of A is then read once per two output blocks and W2 in 512-byte row pieces (-12 % on this product for
+      // 8 192 tokens over 64 experts at d = 512; the other three token-row products did not gain)
+      if (small && !a.plain && 2LL * a.groups_est * big_minor >= 128 && db >= 2) {
+        launch_variant<OP, 1, 2, 2, 8>(p, a.r_max, big_minor, s);
         return;
       }
     }

@@ -43,6 +43,8 @@ def test_tiny_benchmark_config():
     small_config("E100_k4", T=700, d=128, h=128, E=100, k=4, seed=107),
     small_config("E256_k8", T=130, d=128, h=128, E=256, k=8, normalize_topk=1, seed=108),
     small_config("more_experts_than_tokens", T=5, d=128, h=128, E=32, k=1, seed=109),
+    small_config("wide_output_few_rows", T=4096, d=1024, h=256, E=8, k=1, seed=110),   # DSD takes 128x256 tiles here
+    small_config("wide_output_odd_blocks", T=3328, d=1152, h=128, E=7, k=1, zipf_s=0.6, seed=111),   # ... with db = 9
 ], ids=lambda c: c.name)
 def test_small_cases(cfg):
     errs, gpu, ref = full_parity(cfg)
