@@ -197,11 +197,13 @@ DMOE_API int dmoe_bsmm_topology(const uint8_t *mask, int block_rows, int block_c
                                 dmoe_topology_t *out, int32_t *nnz_out);
 
 /* Enqueue one product (table above) on `stream`; asynchronous.  `topo` must come from dmoe_bsmm_topology with the same
- * block_rows and block_cols.  Rows of S without blocks give zero rows of the DSD / DSD^T output, columns without
+ * block_rows and block_cols, and `nnz` is the number of nonzero blocks it reported: SDD and SDD^T launch one workgroup
+ * per nonzero block and find its row through the per-block row indices (Section 5.1.3), so their cost follows nnz and
+ * not block_rows * block_cols.  Rows of S without blocks give zero rows of the DSD / DSD^T output, columns without
  * blocks zero rows of the DS^TD output and zero columns of the DD^TS / DDS output.
  * Errors: DMOE_EINVAL (unknown op, NULL or misaligned pointer, dense not a multiple of 128), DMOE_ELAUNCH.       */
-DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int block_cols, int dense, const void *a,
-                       const void *b, void *out, void *stream);
+DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int block_cols, int nnz, int dense,
+                       const void *a, const void *b, void *out, void *stream);
 
 /* Measurement aid: runs a register-only loop of v_mfma_f32_32x32x16_bf16 (four waves per SIMD on 256 CUs, no memory
  * traffic) on `stream`, waits for it (this call SYNCHRONISES) and returns the rate in TFLOP/s: the matrix-pipe peak

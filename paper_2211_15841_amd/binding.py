@@ -66,8 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_bsmm_sizes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(c_size_t)]
     lib.dmoe_bsmm_topology.argtypes = [c_void_p, ctypes.c_int, ctypes.c_int, c_void_p, c_size_t,
                                        POINTER(DMoETopology), POINTER(c_int32)]
-    lib.dmoe_bsmm.argtypes = [ctypes.c_int, POINTER(DMoETopology), ctypes.c_int, ctypes.c_int, ctypes.c_int, c_void_p,
-                              c_void_p, c_void_p, c_void_p]
+    lib.dmoe_bsmm.argtypes = [ctypes.c_int, POINTER(DMoETopology), ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                              c_void_p, c_void_p, c_void_p, c_void_p]
     lib.dmoe_probe_mfma_tflops.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
@@ -167,8 +167,8 @@ def dmoe_bsmm_topology(mask, topology_mem, nbytes: int):
     return topo, nnz.value
 
 
-def dmoe_bsmm(op: int, topo, block_rows: int, block_cols: int, dense: int, a, b, out, stream=None):
-    _check(load_library().dmoe_bsmm(op, byref(topo), block_rows, block_cols, dense, _ptr(a), _ptr(b), _ptr(out),
+def dmoe_bsmm(op: int, topo, block_rows: int, block_cols: int, nnz: int, dense: int, a, b, out, stream=None):
+    _check(load_library().dmoe_bsmm(op, byref(topo), block_rows, block_cols, nnz, dense, _ptr(a), _ptr(b), _ptr(out),
                                     _stream(stream)))
 
 
@@ -189,39 +189,39 @@ class BlockSparse:
 
     def sdd(self, x, w, stream=None):        # x [M, D], w [D, N] -> S [nnz, 128, 128]
         out = self._out(max(self.nnz, 1), 128, 128)
-        dmoe_bsmm(OP_SDD, self.topo, self.rows, self.cols, x.shape[1], x, w, out, stream)
+        dmoe_bsmm(OP_SDD, self.topo, self.rows, self.cols, self.nnz, x.shape[1], x, w, out, stream)
         return out[:self.nnz]
 
     def sddt(self, x, w, stream=None):       # x [M, D], w [N, D] -> S
         out = self._out(max(self.nnz, 1), 128, 128)
-        dmoe_bsmm(OP_SDDT, self.topo, self.rows, self.cols, x.shape[1], x, w, out, stream)
+        dmoe_bsmm(OP_SDDT, self.topo, self.rows, self.cols, self.nnz, x.shape[1], x, w, out, stream)
         return out[:self.nnz]
 
     def dsd(self, s, w, stream=None):        # s [nnz, 128, 128], w [N, D] -> [M, D]
         out = self._out(self.rows * 128, w.shape[1])
-        dmoe_bsmm(OP_DSD, self.topo, self.rows, self.cols, w.shape[1], s, w, out, stream)
+        dmoe_bsmm(OP_DSD, self.topo, self.rows, self.cols, self.nnz, w.shape[1], s, w, out, stream)
         return out
 
     def dsdt(self, s, w, stream=None):       # w [D, N] -> [M, D]
         out = self._out(self.rows * 128, w.shape[0])
-        dmoe_bsmm(OP_DSDT, self.topo, self.rows, self.cols, w.shape[0], s, w, out, stream)
+        dmoe_bsmm(OP_DSDT, self.topo, self.rows, self.cols, self.nnz, w.shape[0], s, w, out, stream)
         return out
 
     def dstd(self, s, x, stream=None):       # x [M, D] -> [N, D]
         out = self._out(self.cols * 128, x.shape[1])
-        dmoe_bsmm(OP_DSTD, self.topo, self.rows, self.cols, x.shape[1], s, x, out, stream)
+        dmoe_bsmm(OP_DSTD, self.topo, self.rows, self.cols, self.nnz, x.shape[1], s, x, out, stream)
         return out
 
     def ddts(self, x, s, stream=None):       # x [M, D] -> [D, N]
         out = self._out(x.shape[1], self.cols * 128)
-        dmoe_bsmm(OP_DDTS, self.topo, self.rows, self.cols, x.shape[1], x, s, out, stream)
+        dmoe_bsmm(OP_DDTS, self.topo, self.rows, self.cols, self.nnz, x.shape[1], x, s, out, stream)
         return out
 
     def dds(self, x, s, stream=None):        # x [D, M] -> [D, N]
         if x.shape[1] != self.rows * 128:
             raise ValueError("x must have %d columns (got %d)" % (self.rows * 128, x.shape[1]))
         out = self._out(x.shape[0], self.cols * 128)
-        dmoe_bsmm(OP_DDS, self.topo, self.rows, self.cols, x.shape[0], x, s, out, stream)
+        dmoe_bsmm(OP_DDS, self.topo, self.rows, self.cols, self.nnz, x.shape[0], x, s, out, stream)
         return out
 
 

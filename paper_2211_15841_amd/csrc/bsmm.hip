@@ -42,6 +42,7 @@ struct BsParams {
   bf16_t* out1;
   const int32_t* row_offsets;
   const int32_t* column_indices;
+  const int32_t* row_indices;         // block-row of every nonzero block (the COO half of the encoding, Section 5.1.3)
   const int32_t* column_offsets_t;
   const int32_t* row_indices_t;
   const int32_t* block_offsets_t;
@@ -58,6 +59,7 @@ struct BsParams {
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
   int ka;                  // DDS: leading dimension of dense_a
+  int coo;                 // 1: SDD / SDD^T take one nonzero block per workgroup, found through row_indices
 };
 
 template <int OP> struct OpLayouts;
@@ -145,9 +147,10 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
   int major, minor, P;
   {
-    const int nminor = kSparseOut ? ncu : nju;
+    const bool coo = kSparseOut && PA * PB == 1 && p.coo;
+    const int nminor = coo ? 1 : kSparseOut ? ncu : nju;
     if constexpr (kRowMajor) {
-      const int majors = PA == 2 ? p.group_offsets[p.E] : p.counts[1];
+      const int majors = coo ? p.counts[2] : PA == 2 ? p.group_offsets[p.E] : p.counts[1];
       P = p.patch > 0 ? p.patch : balanced_patch((majors + 3) / 4 * 4 * nminor, -p.patch);
     } else {
       P = p.sched[1];                               // 1 or 16, chosen with the routing in hand (offsets_kernel)
@@ -161,31 +164,43 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   int nk = 0;
   int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jd0 = 0;
   if constexpr (kRowMajor) {
-    if constexpr (PA == 2) {
-      if (major >= p.group_offsets[p.E]) return;
-      const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
-      r0 = rg >> 1;
-      a_ok[1] = rg & 1;
-    } else {
-      if (major >= p.counts[1]) return;
-      r0 = major;
-    }
-    r1 = a_ok[1] ? r0 + 1 : r0;
-    first0 = p.row_offsets[r0];
-    first1 = p.row_offsets[r1];
-    const int nblk = p.row_offsets[r0 + 1] - first0;
-    if constexpr (kSparseOut) {
-      if (PB * minor >= nblk) return;
-      b_ok[1] = PB == 2 && 2 * minor + 1 < nblk;
-      first0 += PB * minor;                         // block (r0, c0); (r0, c1) is the next one
-      first1 += PB * minor;
-      c0 = p.column_indices[first0];
-      c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
+    bool is_coo = false;
+    if constexpr (kSparseOut && PA * PB == 1) is_coo = p.coo;
+    if (is_coo) {
+      // A general mask may have any number of blocks in a row; the per-block row index of the hybrid encoding lets
+      // SDD give every nonzero block its own workgroup without searching the row offsets (Section 5.1.3).
+      if (major >= p.counts[2]) return;
+      first0 = first1 = major;
+      r0 = r1 = p.row_indices[major];
+      c0 = c1 = p.column_indices[major];
       nk = d / BK;
     } else {
-      jd0 = PB * minor;
-      b_ok[1] = PB == 2 && jd0 + 1 < db;
-      nk = kSub * nblk;
+      if constexpr (PA == 2) {
+        if (major >= p.group_offsets[p.E]) return;
+        const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
+        r0 = rg >> 1;
+        a_ok[1] = rg & 1;
+      } else {
+        if (major >= p.counts[1]) return;
+        r0 = major;
+      }
+      r1 = a_ok[1] ? r0 + 1 : r0;
+      first0 = p.row_offsets[r0];
+      first1 = p.row_offsets[r1];
+      const int nblk = p.row_offsets[r0 + 1] - first0;
+      if constexpr (kSparseOut) {
+        if (PB * minor >= nblk) return;
+        b_ok[1] = PB == 2 && 2 * minor + 1 < nblk;
+        first0 += PB * minor;                         // block (r0, c0); (r0, c1) is the next one
+        first1 += PB * minor;
+        c0 = p.column_indices[first0];
+        c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
+        nk = d / BK;
+      } else {
+        jd0 = PB * minor;
+        b_ok[1] = PB == 2 && jd0 + 1 < db;
+        nk = kSub * nblk;
+      }
     }
   } else {
     if (major >= p.E * ncu) return;
@@ -606,6 +621,12 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
         return;
       }
     }
+    if constexpr (sparse_out) {
+      if (small && a.coo) {                       // general masks: one workgroup per nonzero block
+        launch_variant<OP, 1, 1, 2, 8>(p, a.nnz, 1, s);
+        return;
+      }
+    }
     if (small) launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
     else       launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
   } else {
@@ -620,7 +641,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.dense_a = a.dense_a;  p.dense_b = a.dense_b;  p.sparse_in = a.sparse_in;
   p.out0 = a.out0;  p.out1 = a.out1;
   const dmoe_topology_t& t = *a.topo;
-  p.row_offsets = t.row_offsets;  p.column_indices = t.column_indices;
+  p.row_offsets = t.row_offsets;  p.column_indices = t.column_indices;  p.row_indices = t.row_indices;
   p.column_offsets_t = t.column_offsets_t;  p.row_indices_t = t.row_indices_t;  p.block_offsets_t = t.block_offsets_t;
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.counts = t.counts;  p.sched = t.sched;
@@ -629,6 +650,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.plain = a.plain;
   p.accum = a.accum;
   p.ka = a.ka;
+  p.coo = a.coo;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless

@@ -131,21 +131,22 @@ int dmoe_bsmm_topology(const uint8_t* mask, int block_rows, int block_cols, void
   return DMOE_OK;
 }
 
-int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_cols, int dense, const void* a,
+int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_cols, int nnz, int dense, const void* a,
               const void* b, void* out, void* stream) {
   if (op < DMOE_OP_SDD || op > DMOE_OP_DDS) return fail(DMOE_EINVAL, "unknown product %d", op);
   if (!topo || !topo->row_offsets || !topo->counts) return fail(DMOE_EINVAL, "topology is NULL or not built");
-  if (int rc = check_mask_dims(block_rows, block_cols, 0)) return rc;
+  if (int rc = check_mask_dims(block_rows, block_cols, nnz)) return rc;
   if (dense < kBlock || dense % kBlock) return fail(DMOE_EINVAL, "dense must be a positive multiple of 128 (got %d)", dense);
   if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32) ||
       (long long)block_rows * kBlock * kBlock >= (1ll << 32))
     return fail(DMOE_EINVAL, "operands too large");
+  if ((op == DMOE_OP_SDD || op == DMOE_OP_SDDT) && nnz == 0) return DMOE_OK;      // no block to write
   if (int rc = check_ptr(a, "a")) return rc;
   if (int rc = check_ptr(b, "b")) return rc;
   if (int rc = check_ptr(out, "out")) return rc;
   BsArgs g{};
   g.topo = topo;  g.d = dense;  g.h = block_cols * kBlock;  g.E = 1;
-  g.r_max = block_rows;  g.g_max = 0;  g.groups_est = 0;  g.force_tile = 1;  g.plain = 1;
+  g.r_max = block_rows;  g.g_max = 0;  g.groups_est = 0;  g.force_tile = 1;  g.plain = 1;  g.coo = 1;  g.nnz = nnz;
   const bf16_t* pa = static_cast<const bf16_t*>(a);
   const bf16_t* pb = static_cast<const bf16_t*>(b);
   g.out0 = static_cast<bf16_t*>(out);

@@ -93,6 +93,8 @@ struct BsArgs {
   int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
   int ka;                  // DDS only: leading dimension of dense_a (= 128 * block rows of S)
   int act;                 // SDD's fused activation: 0 exact (erf) GELU, 1 tanh form
+  int coo;                 // 1 (general masks): SDD / SDD^T enumerate the nonzero blocks through row_indices
+  int nnz;                 // ... and this many of them
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))

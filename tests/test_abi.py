@@ -103,13 +103,16 @@ def test_general_products_validate_their_arguments():
     assert lib.dmoe_bsmm_topology(mask, 2, 2, 256 + 8, 4096, ctypes.byref(topo), None) != 0       # misaligned
     assert lib.dmoe_bsmm_topology(mask, 2, 2, 256, 16, ctypes.byref(topo), None) != 0             # too small
     assert "needs" in dm.dmoe_last_error()
-    assert lib.dmoe_bsmm(9, ctypes.byref(topo), 2, 2, 128, 256, 256, 256, None) != 0              # unknown product
-    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 128, 256, 256, 256, None) != 0      # topology not built
+    assert lib.dmoe_bsmm(9, ctypes.byref(topo), 2, 2, 2, 128, 256, 256, 256, None) != 0              # unknown product
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 2, 128, 256, 256, 256, None) != 0   # topology not built
     topo.row_offsets = 256
     topo.counts = 256
-    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 100, 256, 256, 256, None) != 0      # dense not a multiple
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 2, 100, 256, 256, 256, None) != 0   # dense not a multiple
     assert "multiple of 128" in dm.dmoe_last_error()
-    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 128, None, 256, 256, None) != 0     # NULL operand
+    assert lib.dmoe_bsmm(dm.OP_SDD, ctypes.byref(topo), 2, 2, 5, 128, 256, 256, 256, None) != 0    # more blocks than the mask has room for
+    assert "nnz" in dm.dmoe_last_error()
+    assert lib.dmoe_bsmm(dm.OP_SDD, ctypes.byref(topo), 2, 2, 0, 128, 256, 256, None, None) == 0    # empty mask: nothing to write
+    assert lib.dmoe_bsmm(dm.OP_DSD, ctypes.byref(topo), 2, 2, 2, 128, None, 256, 256, None) != 0  # NULL operand
 
 
 def test_a_missing_library_fails_loudly(monkeypatch, tmp_path):
