@@ -32,14 +32,14 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "sdd"): 279949312, ("xs", "dsd"): 218877338, ("xs", "sddt"): 279871693,
-    ("xs", "dstd"): 193072230, ("xs", "dsdt"): 217856000, ("xs", "ddts"): 193143910,
-    ("small_zipf1.0", "sdd"): 638781440, ("small_zipf1.0", "dsd"): 543215411, ("small_zipf1.0", "sddt"): 638287872,
-    ("small_zipf1.0", "dstd"): 1007989146, ("small_zipf1.0", "dsdt"): 542797005, ("small_zipf1.0", "ddts"): 984878490,
-    ("medium_zipf1.2_top2", "sdd"): 2359126630, ("medium_zipf1.2_top2", "dsd"): 2590814003, ("medium_zipf1.2_top2", "sddt"): 2365401702,
-    ("medium_zipf1.2_top2", "dstd"): 2813959578, ("medium_zipf1.2_top2", "dsdt"): 2616198758, ("medium_zipf1.2_top2", "ddts"): 2814806528,
-    ("large_expert_top2", "sdd"): 17414645350, ("large_expert_top2", "dsd"): 13780411187, ("large_expert_top2", "sddt"): 18134873498,
-    ("large_expert_top2", "dstd"): 13422674125, ("large_expert_top2", "dsdt"): 15500668109, ("large_expert_top2", "ddts"): 13380331520,
+    ("xs", "sdd"): 279971430, ("xs", "dsd"): 217806029, ("xs", "sddt"): 279879066,
+    ("xs", "dstd"): 186814259, ("xs", "dsdt"): 217932800, ("xs", "ddts"): 186825114,
+    ("small_zipf1.0", "sdd"): 638619648, ("small_zipf1.0", "dsd"): 543279923, ("small_zipf1.0", "sddt"): 638298522,
+    ("small_zipf1.0", "dstd"): 1004661350, ("small_zipf1.0", "dsdt"): 542840422, ("small_zipf1.0", "ddts"): 973299712,
+    ("medium_zipf1.2_top2", "sdd"): 2359846298, ("medium_zipf1.2_top2", "dsd"): 2597350195, ("medium_zipf1.2_top2", "sddt"): 2363067187,
+    ("medium_zipf1.2_top2", "dstd"): 2777749094, ("medium_zipf1.2_top2", "dsdt"): 2618416742, ("medium_zipf1.2_top2", "ddts"): 2777421619,
+    ("large_expert_top2", "sdd"): 17531976294, ("large_expert_top2", "dsd"): 13474023219, ("large_expert_top2", "sddt"): 17692413133,
+    ("large_expert_top2", "dstd"): 13536413901, ("large_expert_top2", "dsdt"): 17553352704, ("large_expert_top2", "ddts"): 13459670016,
 }
 
 
