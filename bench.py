@@ -5,9 +5,12 @@ Prints ONE JSON line.  `value` is useful TFLOP/s = 12*T*k*d*h / time (six block-
 flops each; padding rows, the router and the permutation kernels are not counted as useful work) with every
 input already resident in HBM.  `roofline` describes the slowest block-sparse product of the step, timed with
 HIP events recorded around that kernel on the stream it runs on, inside the timed steps.  `cpu_baseline` is the
-CPU oracle (fp64 numpy) timed once on the same workload on the host cores.
+CPU oracle (fp64 numpy) timed on the host cores, on the whole workload when that takes seconds and on a stated
+slice of it (a prefix of the batch's tokens against the full expert weights) for the largest configuration.
+The headline is the largest configuration, large_expert_top2; the other four are reported beside it under
+`other_workloads`, each with its own timed steps (median and mean) and roofline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config xs] [--also small_zipf1.0,...] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large_expert_top2] [--also tiny,xs,...] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -82,6 +85,9 @@ def algorithmic_bytes(stage: str, T, k, d, h, E, P, active) -> float:
     }[stage]
 
 
+CPU_SLICE_TOKENS = 512      # tokens of the batch that the oracle is timed on when the whole workload would take minutes
+
+
 def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=False):
     import numpy as np
     import torch
@@ -141,14 +147,19 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
         arr = EvArr()
         arr[2 * di], arr[2 * di + 1] = hipev.create(), hipev.create()
         ev_sets.append(arr)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # step boundaries, for the median
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for arr in ev_sets:
+    marks[0].record()
+    for i, arr in enumerate(ev_sets):
         dm.dmoe_set_stage_events(arr)
         step()
+        marks[i + 1].record()
     dm.dmoe_set_stage_events(None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    median_ms = 0.5 * (step_ms[(steps - 1) // 2] + step_ms[steps // 2])
     kernel_ms = sum(hipev.elapsed_ms(a[2 * di], a[2 * di + 1]) for a in ev_sets) / steps
     for a in ev_sets:
         hipev.hip.hipEventDestroy(a[2 * di]); hipev.hip.hipEventDestroy(a[2 * di + 1])
@@ -161,7 +172,9 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
     ms = elapsed * 1e3 / steps
     useful = cfg.useful_flops
     res = {
-        "workload": cfg.name, "ms_per_step": ms, "useful_tflops": useful / (ms * 1e-3) / 1e12,
+        "workload": cfg.name, "steps": steps, "ms_per_step": ms, "ms_per_step_median": median_ms,
+        "useful_tflops": useful / (ms * 1e-3) / 1e12,
+        "useful_tflops_median": useful / (median_ms * 1e-3) / 1e12,
         "pct_mfma_peak": 100.0 * useful / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "padded_tflops": 12.0 * P * d * h / (ms * 1e-3) / 1e12,
         "P": P, "nnz_blocks": nnz, "active_experts": active, "max_tokens_per_expert": int(n_e.max()),
@@ -187,25 +200,36 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
     if with_cpu:
         from threadpoolctl import threadpool_info
         from oracle import dmoe_oracle as orc
-        # the whole workload, repeated until about ten seconds of CPU work have been timed (at most eight passes)
+        # The oracle as it stands: route + permute + topology + forward + backward in fp64 numpy.  The whole workload
+        # when that is seconds of work (repeated until about ten seconds have been timed, at most eight passes);
+        # otherwise a slice of it: the first CPU_SLICE_TOKENS tokens of the batch, routed by the same router, against
+        # the full expert weights (each token's rows are independent dense computations, so a prefix of the batch is
+        # the same work per token; its useful flops are 12 * tokens * k * d * h).
+        whole = useful <= 5e12
+        n_tok = T if whole else min(T, CPU_SLICE_TOKENS)
+        xs_, dys_ = inp["x"][:n_tok], inp["dy"][:n_tok]
         cpu_s, passes = 0.0, 0
-        while passes < 8 and (passes == 0 or cpu_s < 10.0):
+        while passes < (8 if whole else 1) and (passes == 0 or cpu_s < 10.0):
             t1 = time.perf_counter()
-            logits, idx, w, p = orc.route(inp["x"], inp["w_router"], inp["router_bias"], k, cfg.normalize_topk)
+            logits, idx, w, p = orc.route(xs_, inp["w_router"], inp["router_bias"], k, cfg.normalize_topk)
             n, off, row_of, token_of = orc.permutation(idx, E)
             orc.topology(off, h)
-            orc.forward(inp["x"], inp["w1"], inp["w2"], idx, w, h)
-            orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], idx, w, p, h, cfg.normalize_topk)
+            orc.forward(xs_, inp["w1"], inp["w2"], idx, w, h)
+            orc.backward(xs_, inp["w_router"], inp["w1"], inp["w2"], dys_, idx, w, p, h, cfg.normalize_topk)
             cpu_s += time.perf_counter() - t1
             passes += 1
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
         cpu_s /= passes
-        # backward() recomputes the forward to get its intermediates: 18*T*k*d*h flops of matmul in total
-        res["cpu_baseline"] = {"value": useful / cpu_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-                               "sample": "the whole %s workload (route + permute + topology + forward + backward, fp64 "
-                                         "numpy), %d passes of %.2f s each, host has %d cpus"
-                                         % (cfg.name, passes, cpu_s, os.cpu_count())}
-        log("[bench] %s: oracle %.2f s on %d threads" % (cfg.name, cpu_s, threads))
+        # backward() recomputes the forward to get its intermediates: 18*tokens*k*d*h flops of matmul in total
+        what = ("the whole %s workload" % cfg.name) if whole else \
+            ("the first %d of the %d tokens of %s (%d assignments) against all %d experts' full weights"
+             % (n_tok, T, cfg.name, n_tok * k, E))
+        res["cpu_baseline"] = {"value": 12.0 * n_tok * k * d * h / cpu_s / 1e12, "unit": "TFLOP/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": "%s (route + permute + topology + forward + backward, fp64 numpy), %d "
+                                         "pass(es) of %.2f s each, host has %d cpus"
+                                         % (what, passes, cpu_s, os.cpu_count())}
+        log("[bench] %s: oracle %.2f s on %d threads (%s)" % (cfg.name, cpu_s, threads, what))
     del ws, x, wr, w1, w2, dy
     torch.cuda.empty_cache()
     return res
@@ -214,12 +238,16 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="xs", help="workload name (see dmoe_inputs.CONFIGS) or 1-based index")
-    ap.add_argument("--also", default="small_zipf1.0,medium_zipf1.2_top2",
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--config", default="large_expert_top2",
+                    help="headline workload: name (see dmoe_inputs.CONFIGS) or 1-based index; default = the largest")
+    ap.add_argument("--also", default="tiny,xs,small_zipf1.0,medium_zipf1.2_top2",
                     help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
+    ap.add_argument("--also-steps", type=int, default=30, help="timed steps of each extra workload (>= 20)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the register-only MFMA peak probe (keeps its kernel out of rocprofv3 summaries)")
     ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2),
                     help="0: the library's own tile choice (default); 1 / 2: force 128x128 / 256x256 tiles (experiments)")
     ap.add_argument("--accumulate", action="store_true",
@@ -251,27 +279,29 @@ def main():
     import paper_2211_15841_amd as dm
     if args.tile_mode:
         dm.dmoe_set_tile_mode(args.tile_mode)
-    measured_peak = dm.dmoe_probe_mfma_tflops()       # register-only MFMA loop on this machine (context for % of peak)
+    # register-only MFMA loop on this machine (context for % of peak); left out of profiled runs with --no-probe
+    measured_peak = None if args.no_probe else dm.dmoe_probe_mfma_tflops()
     hipev = HipEvents()
     cfg = pick(args.config)
     main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu, accumulate=args.accumulate)
     others = []
     for name in [n for n in args.also.split(",") if n and n != cfg.name]:
-        others.append(run_config(pick(name), max(5, args.steps // 5), max(4, args.warmup // 2), hipev, with_cpu=False,
+        others.append(run_config(pick(name), max(20, args.also_steps), max(6, args.warmup), hipev, with_cpu=False,
                                  accumulate=args.accumulate))
 
     line = {
         "metric": "dMoE FFN fwd+bwd useful TFLOP/s (bf16) + % MFMA peak, 1 MI355X",
         "value": main_res["useful_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "ms_per_step_median": main_res["ms_per_step_median"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "num_tokens": cfg.num_tokens, "d_model": cfg.d_model,
                    "ffn_hidden": cfg.ffn_hidden, "num_experts": cfg.num_experts, "top_k": cfg.top_k,
                    "block": 128, "routing": "zipf(%.1f)-biased router" % cfg.zipf_s if cfg.zipf_s else "random router"},
         "backward": "dmoe_backward_accumulate (fp32 accumulators)" if args.accumulate else "dmoe_backward",
         "pct_mfma_peak": main_res["pct_mfma_peak"],
-        "mfma_peak_measured_tflops": round(measured_peak, 1),
-        "pct_mfma_peak_measured": round(100.0 * main_res["useful_tflops"] / measured_peak, 2),
+        "mfma_peak_measured_tflops": round(measured_peak, 1) if measured_peak else None,
+        "pct_mfma_peak_measured": round(100.0 * main_res["useful_tflops"] / measured_peak, 2) if measured_peak else None,
         "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "roofline_kernel": main_res["roofline"]["kernel"], "roofline_kernel_ms": main_res["roofline"]["kernel_ms"],
         "cpu_baseline": main_res.get("cpu_baseline"),

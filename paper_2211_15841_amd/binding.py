@@ -246,23 +246,49 @@ def dmoe_set_stage_events(events_array):
 class Workspace:
     """Caller-side buffers for one layer configuration, allocated once with torch (device memory only)."""
 
+    GUARD_BYTE = 0xA5
+
     def __init__(self, num_tokens, d_model, ffn_hidden, num_experts, top_k, normalize_topk=0, device="cuda:0",
-                 activation=0):
+                 activation=0, guard_bytes=0):
+        """guard_bytes > 0 (tests): every buffer the library writes sits between two guard zones of that many bytes
+        holding a fixed pattern; check_guards() then tells whether any kernel wrote outside its buffer."""
         self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, activation, normalize_topk)
         self.device = torch.device(device)
         self.sizes = dmoe_sizes(self.cfg)
-        u8 = dict(dtype=torch.uint8, device=self.device)
-        self.topology_mem = torch.empty(self.sizes["topology_bytes"], **u8)
-        self.saved = torch.empty(self.sizes["saved_bytes"], **u8)
-        self.scratch = torch.empty(self.sizes["scratch_bytes"], **u8)
+        self.guard_bytes = (int(guard_bytes) + 255) // 256 * 256
+        self._guarded = []
+        self.topology_mem = self._alloc(self.sizes["topology_bytes"], "topology")
+        self.saved = self._alloc(self.sizes["saved_bytes"], "saved")
+        self.scratch = self._alloc(self.sizes["scratch_bytes"], "scratch")
         self.topo = dmoe_topology_bind(self.cfg, self.topology_mem, self.sizes["topology_bytes"])
         T, d, h, E = num_tokens, d_model, ffn_hidden, num_experts
-        bf = dict(dtype=torch.bfloat16, device=self.device)
-        self.y = torch.empty(T, d, **bf)
-        self.dx = torch.empty(T, d, **bf)
-        self.dw1 = torch.empty(d, E * h, **bf)
-        self.dw2 = torch.empty(E * h, d, **bf)
-        self.dw_router = torch.empty(d, E, dtype=torch.float32, device=self.device)
+        bf = torch.bfloat16
+        self.y = self._alloc(T * d * 2, "y").view(bf).view(T, d)
+        self.dx = self._alloc(T * d * 2, "dx").view(bf).view(T, d)
+        self.dw1 = self._alloc(d * E * h * 2, "dw1").view(bf).view(d, E * h)
+        self.dw2 = self._alloc(E * h * d * 2, "dw2").view(bf).view(E * h, d)
+        self.dw_router = self._alloc(d * E * 4, "dw_router").view(torch.float32).view(d, E)
+
+    def _alloc(self, nbytes, name):
+        g = self.guard_bytes
+        if not g:
+            return torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        body = (nbytes + 255) // 256 * 256
+        whole = torch.full((body + 2 * g,), self.GUARD_BYTE, dtype=torch.uint8, device=self.device)
+        self._guarded.append((name, whole, g, nbytes))
+        return whole[g:g + nbytes]
+
+    def check_guards(self):
+        """Raises if any byte of a guard zone (or of the alignment tail behind a buffer) has changed."""
+        torch.cuda.synchronize(self.device)
+        for name, whole, g, nbytes in self._guarded:
+            lo, hi = whole[:g], whole[g + nbytes:]
+            for side, z in (("below", lo), ("above", hi)):
+                bad = (z != self.GUARD_BYTE).nonzero()
+                if bad.numel():
+                    first = int(bad[0]) - (g if side == "below" else 0)
+                    raise DMoEError("%d bytes written %s buffer '%s' (first at offset %+d from its %s)"
+                                    % (bad.numel(), side, name, first, "start" if side == "below" else "end"))
 
     # -- the three calls of the layer ---------------------------------------------------------------------
     def topology(self, x, w_router, router_bias=None, stream=None):

@@ -1,6 +1,7 @@
 // C ABI of the dMoE library (declared in include/dmoe.h): validation, buffer carving, and the order in which
 // the kernels of one layer pass are enqueued.  Nothing here synchronises or allocates device memory.
 #include "common.h"
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -9,7 +10,8 @@ namespace dmoe {
 
 static thread_local char g_err[512] = "";
 static thread_local hipEvent_t* g_events = nullptr;
-static int g_force_tile = 0;
+static thread_local int g_pending = DMOE_OK;   // an error found by a launcher, reported by the next launch_status()
+static std::atomic<int> g_force_tile{0};
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -17,6 +19,14 @@ int fail(int code, const char* fmt, ...) {
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
   return code;
+}
+
+void fail_pending(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  g_pending = code;
 }
 
 static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -129,6 +139,11 @@ static int check_topo(const dmoe_topology_t* t) {
 }
 int launch_status() {
   const hipError_t e = hipGetLastError();
+  if (g_pending != DMOE_OK) {
+    const int rc = g_pending;
+    g_pending = DMOE_OK;
+    return rc;
+  }
   if (e != hipSuccess) return fail(DMOE_ELAUNCH, "HIP error while enqueueing: %s", hipGetErrorString(e));
   return DMOE_OK;
 }
@@ -233,7 +248,7 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
 
   BsArgs a{};
   a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max; a.r_max = m.r_max;
-  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
+  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile.load(std::memory_order_relaxed);
   ev.begin(DMOE_STAGE_SDD);
   a.dense_a = xp; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = nullptr; a.out0 = hval; a.out1 = aval;
   a.act = cfg->activation;
@@ -298,7 +313,7 @@ static int backward_impl(const dmoe_config* cfg, const void* x, const void* w_ro
 
   BsArgs a{};
   a.topo = topo; a.d = m.d; a.h = m.h; a.E = m.E; a.g_max = m.g_max; a.r_max = m.r_max;
-  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile;
+  a.groups_est = (m.F + 255) / 256; a.force_tile = g_force_tile.load(std::memory_order_relaxed);
 
   ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * G with G = gelu'(H) kept by forward
   a.dense_a = dyp; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = hval; a.out0 = dh; a.out1 = nullptr;
@@ -362,7 +377,7 @@ int dmoe_set_stage_events(void* events) {
 
 int dmoe_set_tile_mode(int mode) {
   if (mode < 0 || mode > 2) return fail(DMOE_EINVAL, "tile mode must be 0 (automatic), 1 (128x128) or 2 (256x256)");
-  g_force_tile = mode;
+  g_force_tile.store(mode, std::memory_order_relaxed);
   return DMOE_OK;
 }
 

@@ -24,6 +24,7 @@
 // lie in memory with the transposing ds_read_b64_tr_b16; both are XOR-swizzled instead of padded.
 #include "common.h"
 #include "mma_tile.h"
+#include <mutex>
 
 namespace dmoe {
 
@@ -327,7 +328,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // stage being computed, which serialises load latency and MFMA work.  Here the waits are explicit.
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
   auto dma16 = [](const bf16_t* g, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
   };
   // part 0 = the A slabs, part 1 = the B slabs (issued at different points of the MFMA loop, see below)
   auto issue_loads = [&](int stage, int part) {
@@ -564,12 +565,19 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
 
 template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
 static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
-  static bool configured = false;
   constexpr int kLds = NS * (PA + PB) * 256 * BK;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    configured = true;
+  // raise the dynamic-LDS limit of this instantiation once per process (thread-safe; a failure is reported by every
+  // later launch of the variant instead of surfacing as an unexplained launch error)
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [] {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  });
+  if (attr_rc != hipSuccess) {
+    fail_pending(DMOE_ELAUNCH, "bsmm<op %d, %dx%d panels>: cannot reserve %d bytes of LDS: %s", OP, PA, PB, kLds,
+         hipGetErrorString(attr_rc));
+    return;
   }
   const int items = ((majors + 3) / 4) * 4 * nminor;          // majors are consumed in runs of 4
   int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD

@@ -105,6 +105,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s);
 
 // ---- host-side helpers shared by the C-ABI source files ----------------------------------------------------------
 int fail(int code, const char* fmt, ...);           // records the message for dmoe_last_error, returns `code`
+void fail_pending(int code, const char* fmt, ...);  // for launchers (void): the next launch_status() returns `code`
 int check_ptr(const void* p, const char* name);     // non-NULL and 256-byte aligned
 int launch_status();                                // DMOE_OK, or DMOE_ELAUNCH with the pending HIP error
 

@@ -10,6 +10,7 @@ from oracle import dmoe_oracle as orc
 
 INDEX_KEYS = ["expert_idx", "tokens_per_expert", "padded_offsets", "row_of", "token_of", "row_offsets",
               "column_indices", "row_indices", "column_offsets_t", "row_indices_t", "block_offsets_t", "counts"]
+GUARD_BYTES = 1 << 20
 REL_TOL = 1e-2          # max |G - O| / max |O| per tensor (bf16 storage, fp32 accumulation)
 
 
@@ -22,8 +23,9 @@ def bf16_to_np(t: torch.Tensor) -> np.ndarray:
 
 
 def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
+    # every buffer the library writes lies between guard zones, checked after the calls: no kernel may write outside
     ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk,
-                      activation=cfg.activation)
+                      activation=cfg.activation, guard_bytes=GUARD_BYTES)
     if poison:      # unwritten regions must not look like zeros (empty experts, padding rows)
         for t in (ws.topology_mem, ws.saved, ws.scratch):
             t.fill_(0xFF)
@@ -44,6 +46,7 @@ def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
         out["dw1"] = bf16_to_np(ws.dw1)
         out["dw2"] = bf16_to_np(ws.dw2)
         out["dw_router"] = ws.dw_router.cpu().numpy().astype(np.float64)
+    ws.check_guards()
     out["ws"] = ws
     return out
 

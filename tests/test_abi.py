@@ -124,3 +124,64 @@ def test_a_missing_library_fails_loudly(monkeypatch, tmp_path):
         binding.load_library()
     with pytest.raises(dm.DMoEError, match="not built"):
         dm.dmoe_sizes(_cfg())
+
+
+# ---- buffer extents at the shape of the Figure-9 problems (65 536 tokens, 8 experts, hidden 512, ffn 2 048) ---------
+FIG9_XS = dict(T=65536, d=512, h=2048, E=8, k=1)
+
+
+@pytest.mark.parametrize("shape", [FIG9_XS, dict(T=8192, d=1536, h=6144, E=8, k=1), dict(T=1000, d=256, h=384, E=7, k=3)],
+                         ids=["fig9_xs", "fig9_medium", "ragged"])
+def test_topology_arrays_are_disjoint_and_inside_the_buffer(shape):
+    """Every array that dmoe_topology_bind carves lies inside the buffer, is 256-byte aligned, and is long enough for
+    the upper bounds of dmoe_sizes -- checked from the pointers the library hands back, for the shape whose run once
+    preceded an unexplained GPU fault."""
+    cfg = _cfg(**shape)
+    s = dm.dmoe_sizes(cfg)
+    fake = 0x7f0000000000
+    topo = dm.dmoe_topology_bind(cfg, fake, s["topology_bytes"])
+    T, E, k, hb = shape["T"], shape["E"], shape["k"], shape["h"] // 128
+    F, P, R, nnz = T * k, s["P_max"], s["P_max"] // 128, s["nnz_max"]
+    g_max = (R + min(E, F) + 1) // 2
+    need = {"expert_idx": F, "weights": F, "logits": T * E, "tokens_per_expert": E, "padded_offsets": E + 1,
+            "row_of": F, "token_of": P, "row_offsets": R + 1, "column_indices": nnz, "row_indices": nnz,
+            "column_offsets_t": E * hb + 1, "row_indices_t": nnz, "block_offsets_t": nnz, "counts": 4,
+            "expert_order": E, "group_offsets": E + 1, "row_group": g_max + 1, "sched": 4}
+    spans = sorted((getattr(topo, n), getattr(topo, n) + 4 * cnt, n) for n, cnt in need.items())
+    assert spans[0][0] == fake and spans[-1][1] <= fake + s["topology_bytes"]
+    for (a0, a1, an), (b0, b1, bn) in zip(spans, spans[1:]):
+        assert a0 % 256 == 0 and a1 <= b0, "%s overlaps %s" % (an, bn)
+
+
+@pytest.mark.parametrize("shape", [FIG9_XS, dict(T=8192, d=512, h=2048, E=64, k=1), dict(T=300, d=128, h=256, E=64, k=2),
+                                   dict(T=40, d=128, h=128, E=64, k=1)], ids=["fig9_xs", "xs", "ragged", "few_tokens"])
+def test_sizes_cover_the_worst_routing(shape):
+    """The padded row count, block-row count, row-group count and block count of ANY routing stay within what
+    dmoe_sizes reports.  Worst cases are built by hand (every expert one row past a multiple of 128, all rows on one
+    expert, perfectly even) and pushed through the oracle's own grouping, which is pinned elsewhere."""
+    import numpy as np
+    from oracle import dmoe_oracle as orc
+    cfg = _cfg(**shape)
+    s = dm.dmoe_sizes(cfg)
+    T, E, k, hb = shape["T"], shape["E"], shape["k"], shape["h"] // 128
+    F = T * k
+    loads = []
+    n = np.zeros(E, dtype=np.int64)                       # as many experts as possible hold 1 (mod 128) rows
+    m = min(E, F)
+    n[:m] = 1
+    rest = F - m
+    n[:m] += (rest // (128 * m)) * 128
+    n[0] += F - n.sum()
+    loads.append(n)
+    one = np.zeros(E, dtype=np.int64); one[E - 1] = F
+    loads.append(one)
+    loads.append(np.full(E, F // E, dtype=np.int64) + (np.arange(E) < F % E))
+    for n in loads:
+        assert n.sum() == F
+        idx = np.repeat(np.arange(E), n).astype(np.int32).reshape(-1, 1)      # one assignment per row, grouped
+        cnt, off, row_of, token_of = orc.permutation(idx, E)
+        P = int(off[-1]); R = P // 128
+        groups = int(sum((int(off[e + 1] - off[e]) // 128 + 1) // 2 for e in range(E)))
+        assert P <= s["P_max"] and R * hb <= s["nnz_max"]
+        assert groups <= (s["P_max"] // 128 + min(E, F) + 1) // 2
+        assert len(token_of) == P and row_of.max() < P
