@@ -112,6 +112,18 @@ DMOE_API int dmoe_topology_bind(const dmoe_config *cfg, void *topology_mem, size
 DMOE_API int dmoe_topology(const dmoe_config *cfg, const void *x, const void *w_router, const float *router_bias,
                   dmoe_topology_t *topo, void *scratch, size_t scratch_bytes, void *stream);
 
+/* dmoe_topology for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same results in *topo (bit for bit),
+ * but the scratch of the call (the per-chunk expert counts, ceil(T*k/256)*E int32) lives in a 1 MiB device array
+ * built into the library instead of a caller buffer; each GPU the library runs on holds that array until the process
+ * ends.  The call allocates and frees nothing.  The device that `stream` belongs to must be the current device.
+ * Limit: ceil(T*k/256) * E * 4 <= 1 048 576 bytes, else DMOE_ENOMEM and nothing is enqueued.  All calls on one GPU
+ * share the one array: calls that overlap in time on the same GPU (different streams, different threads) race; calls
+ * on one stream are ordered and safe (every call rewrites the part of the array it reads).  Other errors as
+ * dmoe_topology, plus DMOE_ELAUNCH if the array's device address cannot be obtained.                            */
+DMOE_API int dmoe_topology_static(const dmoe_config *cfg, const void *x, const void *w_router,
+                                  const float *router_bias, dmoe_topology_t *topo, void *stream);
+
 /* Steps (3)-(5) of Figure 6: padded gather, SDD (+GELU), DSD, padded scatter scaled by the confidences and
  * summed over the k slots (Section 2.4).  Writes y [T,d] bf16 and `saved` (>= saved_bytes).                    */
 DMOE_API int dmoe_forward(const dmoe_config *cfg, const void *x, const void *w1, const void *w2,

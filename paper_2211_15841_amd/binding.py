@@ -54,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_topology_bind.argtypes = [POINTER(DMoEConfig), c_void_p, c_size_t, POINTER(DMoETopology)]
     lib.dmoe_topology.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, POINTER(DMoETopology), c_void_p,
                                   c_size_t, c_void_p]
+    lib.dmoe_topology_static.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, POINTER(DMoETopology),
+                                         c_void_p]
     lib.dmoe_forward.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, POINTER(DMoETopology), c_void_p,
                                  c_void_p, c_size_t, c_void_p, c_size_t, c_void_p]
     lib.dmoe_backward.argtypes = [POINTER(DMoEConfig), c_void_p, c_void_p, c_void_p, c_void_p, POINTER(DMoETopology),
@@ -70,7 +72,7 @@ def load_library() -> ctypes.CDLL:
                               c_void_p, c_void_p, c_void_p, c_void_p]
     lib.dmoe_probe_mfma_tflops.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
     lib.dmoe_last_error.restype = c_char_p
-    for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_forward", "dmoe_backward",
+    for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_topology_static", "dmoe_forward", "dmoe_backward",
                  "dmoe_backward_accumulate", "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
                  "dmoe_bsmm_topology", "dmoe_bsmm", "dmoe_probe_mfma_tflops"):
         getattr(lib, name).restype = ctypes.c_int
@@ -118,6 +120,11 @@ def dmoe_topology_bind(cfg: DMoEConfig, topology_mem, nbytes: int) -> DMoETopolo
 def dmoe_topology(cfg, x, w_router, router_bias, topo, scratch, scratch_bytes, stream=None):
     _check(load_library().dmoe_topology(byref(cfg), _ptr(x), _ptr(w_router), _ptr(router_bias), byref(topo),
                                         _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def dmoe_topology_static(cfg, x, w_router, router_bias, topo, stream=None):
+    _check(load_library().dmoe_topology_static(byref(cfg), _ptr(x), _ptr(w_router), _ptr(router_bias), byref(topo),
+                                               _stream(stream)))
 
 
 def dmoe_forward(cfg, x, w1, w2, topo, y, saved, saved_bytes, scratch, scratch_bytes, stream=None):
@@ -293,6 +300,10 @@ class Workspace:
     # -- the three calls of the layer ---------------------------------------------------------------------
     def topology(self, x, w_router, router_bias=None, stream=None):
         dmoe_topology(self.cfg, x, w_router, router_bias, self.topo, self.scratch, self.sizes["scratch_bytes"], stream)
+
+    def topology_static(self, x, w_router, router_bias=None, stream=None):
+        """dmoe_topology with the library's built-in scratch instead of this workspace's."""
+        dmoe_topology_static(self.cfg, x, w_router, router_bias, self.topo, stream)
 
     def forward(self, x, w1, w2, stream=None):
         dmoe_forward(self.cfg, x, w1, w2, self.topo, self.y, self.saved, self.sizes["saved_bytes"], self.scratch,

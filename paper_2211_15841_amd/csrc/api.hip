@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 namespace dmoe {
 
@@ -217,6 +218,55 @@ int dmoe_topology(const dmoe_config* cfg, const void* x, const void* w_router, c
   ev.begin(DMOE_STAGE_TOPOLOGY);
   launch_make_topology(*cfg, *topo, m.p_max, m.nnz_max, s);
   ev.end(DMOE_STAGE_TOPOLOGY);
+  return launch_status();
+}
+
+// ---- dmoe_topology for callers that cannot allocate or hand over a workspace ------------------------------------
+// The only scratch dmoe_topology uses is the table of per-chunk expert counts ([ceil(T*k/256)][E] int32), which the
+// first grouping kernel writes in full before anything reads it, so nothing has to be cleared between calls.  Here it
+// lives in a file-scope device array; the host code below never passes the array's name to the GPU (in host code that
+// name is only a handle) but the device address that hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char static_scratch_mem[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static void* g_static_ptr[kMaxDevices] = {};         // per device: each GPU holds its own copy at its own address
+
+static int static_scratch_for_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(DMOE_ELAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(DMOE_EINVAL, "device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch_mem));
+    if (e != hipSuccess || !ptr)
+      return fail(DMOE_ELAUNCH, "hipGetSymbolAddress(static scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return DMOE_OK;
+}
+
+int dmoe_topology_static(const dmoe_config* cfg, const void* x, const void* w_router, const float* router_bias,
+                         dmoe_topology_t* topo, void* stream) {
+  Dims m;
+  if (int rc = check_config(cfg, &m)) return rc;
+  if (int rc = check_ptr(x, "x")) return rc;
+  if (int rc = check_ptr(w_router, "w_router")) return rc;
+  if (int rc = check_topo(topo)) return rc;
+  const size_t need = (size_t)m.nchunks * m.E * 4;
+  if (need > kStaticScratchBytes)
+    return fail(DMOE_ENOMEM, "dmoe_topology_static: ceil(T*k/256)*E*4 = %zu bytes of chunk counts exceed the built-in "
+                "%zu-byte scratch; use dmoe_topology with a caller-provided scratch", need, kStaticScratchBytes);
+  void* chunk_counts = nullptr;
+  if (int rc = static_scratch_for_current_device(&chunk_counts)) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  launch_router(*cfg, static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w_router), router_bias, *topo, s);
+  launch_sort(*cfg, *topo, static_cast<int32_t*>(chunk_counts), m.p_max, s);
+  launch_make_topology(*cfg, *topo, m.p_max, m.nnz_max, s);
   return launch_status();
 }
 
