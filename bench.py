@@ -85,7 +85,7 @@ def algorithmic_bytes(stage: str, T, k, d, h, E, P, active) -> float:
     }[stage]
 
 
-CPU_SLICE_TOKENS = 512      # tokens of the batch that the oracle is timed on when the whole workload would take minutes
+CPU_SLICE_TOKENS = 2048     # tokens of the batch that the oracle is timed on when the whole workload would take minutes
 
 
 def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=False):
