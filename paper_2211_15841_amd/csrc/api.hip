@@ -61,7 +61,7 @@ static int check_config(const dmoe_config* c, Dims* out) {
   if (pm / kBlock * m.hb >= (1ll << 27)) return fail(DMOE_EINVAL, "too many nonzero blocks");
   m.p_max = (int)pm; m.r_max = m.p_max / kBlock; m.nnz_max = m.r_max * m.hb;
   m.g_max = (int)((m.r_max + nonempty + 1) / 2);   // sum_e ceil(rows_e / 2)
-  if ((long long)m.E * m.h * kBlock >= (1ll << 32)) return fail(DMOE_EINVAL, "num_experts*ffn_hidden too large");
+  if ((long long)m.E * m.h * kBlock >= (1ll << 31)) return fail(DMOE_EINVAL, "num_experts*ffn_hidden too large");   // byte offsets inside a 128-row slab are 32-bit
   m.nchunks = (m.F + 255) / 256;
   m.npart = router_bwd_num_partials(*c);
   if (out) *out = m;

@@ -137,6 +137,7 @@ int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_col
   if (!topo || !topo->row_offsets || !topo->counts) return fail(DMOE_EINVAL, "topology is NULL or not built");
   if (int rc = check_mask_dims(block_rows, block_cols, nnz)) return rc;
   if (dense < kBlock || dense % kBlock) return fail(DMOE_EINVAL, "dense must be a positive multiple of 128 (got %d)", dense);
+  if (dense >= (1 << 24)) return fail(DMOE_EINVAL, "dense must stay below 2^24 (got %d)", dense);   // 32-bit byte offsets in a slab
   if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32) ||
       (long long)block_rows * kBlock * kBlock >= (1ll << 32))
     return fail(DMOE_EINVAL, "operands too large");
