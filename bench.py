@@ -281,6 +281,9 @@ def main():
         dm.dmoe_set_tile_mode(args.tile_mode)
     # register-only MFMA loop on this machine (context for % of peak); left out of profiled runs with --no-probe
     measured_peak = None if args.no_probe else dm.dmoe_probe_mfma_tflops()
+    # the same instruction on operands that toggle like real data, after half a second of sustained load: the rate
+    # and shader clock the device holds under its power management (the published peak assumes 2.4 GHz)
+    sustained = (None, None) if args.no_probe else dm.dmoe_probe_mfma_sustained(0.5)
     hipev = HipEvents()
     cfg = pick(args.config)
     main_res = run_config(cfg, args.steps, args.warmup, hipev, with_cpu=not args.no_cpu, accumulate=args.accumulate)
@@ -302,6 +305,9 @@ def main():
         "pct_mfma_peak": main_res["pct_mfma_peak"],
         "mfma_peak_measured_tflops": round(measured_peak, 1) if measured_peak else None,
         "pct_mfma_peak_measured": round(100.0 * main_res["useful_tflops"] / measured_peak, 2) if measured_peak else None,
+        "mfma_sustained_tflops": round(sustained[0], 1) if sustained[0] else None,
+        "mfma_sustained_shader_ghz": round(sustained[1], 3) if sustained[0] else None,
+        "pct_mfma_sustained": round(100.0 * main_res["useful_tflops"] / sustained[0], 2) if sustained[0] else None,
         "roofline": {k: main_res["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "roofline_kernel": main_res["roofline"]["kernel"], "roofline_kernel_ms": main_res["roofline"]["kernel_ms"],
         "cpu_baseline": main_res.get("cpu_baseline"),

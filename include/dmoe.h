@@ -152,6 +152,12 @@ DMOE_API int dmoe_backward_accumulate(const dmoe_config *cfg, const void *x, con
 /* Test helper: waits for `stream` and copies counts[4] (P, R, nnz, 0) to host memory `out4`. */
 DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out4, void *stream);
 
+/* Test helper: byte offset, inside the `scratch` buffer of `cfg`, of one of the intermediates that dmoe_backward leaves
+ * there ("dyp": permuted, confidence-scaled upstream gradient [P_max,d] bf16; "dh": gradient of the hidden blocks;
+ * "dxp": permuted input gradient [P_max,d] bf16; "dweights": [T*k] fp32; "dlogits": gradient of the router scores
+ * [T,E] fp32; "partials"; "chunk_counts").  Host pointers; no GPU work.  Errors: DMOE_EINVAL (unknown name).       */
+DMOE_API int dmoe_debug_scratch_offset(const dmoe_config *cfg, const char *region, size_t *offset);
+
 /* Timing helper for benchmarks: when `events` (host array of 2*DMOE_NUM_STAGES hipEvent_t, created by the
  * caller) is non-NULL, the next calls on this thread record an event before and after each stage's kernels
  * on the stream they are launched on.  Pass NULL to switch it off.  Stage numbers are DMOE_STAGE_*.           */
@@ -222,6 +228,15 @@ DMOE_API int dmoe_bsmm(int op, const dmoe_topology_t *topo, int block_rows, int 
  * this device delivers at the clock it sustains, to set beside the published 2.5 PFLOP/s.  `scratch4`: device, >= 4
  * bytes, 256-byte aligned (never written).  Errors: DMOE_EINVAL, DMOE_ELAUNCH.                                  */
 DMOE_API int dmoe_probe_mfma_tflops(float *tflops, void *scratch4, void *stream);
+
+/* Measurement aid: the rate the matrix pipes SUSTAIN.  Runs the same instruction shaped like a wave of the 256x256 tile
+ * (4 x 2 fragments, eight accumulators, two waves per SIMD on 256 CUs, no memory traffic) on pseudo-random operands
+ * whose mantissa bits change every iteration, launch after launch for about `seconds` (0 < seconds <= 5), and reports
+ * the rate of the last five launches in TFLOP/s together with the shader clock observed inside the kernel (shader-clock
+ * counter against the 100 MHz wall counter) in GHz.  The published peak assumes 2.4 GHz; under sustained matrix load
+ * the device runs slower, and this is the ceiling the block-sparse products can be set against.  This call SYNCHRONISES.
+ * `scratch64`: device, >= 64 bytes, 256-byte aligned (overwritten).  Errors: DMOE_EINVAL, DMOE_ELAUNCH.            */
+DMOE_API int dmoe_probe_mfma_sustained(float *tflops, float *shader_ghz, float seconds, void *scratch64, void *stream);
 
 /* Message for the last error returned on this thread (host pointer to static thread-local storage). */
 DMOE_API const char *dmoe_last_error(void);

@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_backward_accumulate.argtypes = lib.dmoe_backward.argtypes
     lib.dmoe_topology_counts_host.argtypes = [POINTER(DMoETopology), POINTER(c_int32), c_void_p]
     lib.dmoe_set_stage_events.argtypes = [c_void_p]
+    lib.dmoe_debug_scratch_offset.argtypes = [POINTER(DMoEConfig), c_char_p, POINTER(c_size_t)]
+    lib.dmoe_debug_scratch_offset.restype = ctypes.c_int
     lib.dmoe_set_tile_mode.argtypes = [ctypes.c_int]
     lib.dmoe_bsmm_sizes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(c_size_t)]
     lib.dmoe_bsmm_topology.argtypes = [c_void_p, ctypes.c_int, ctypes.c_int, c_void_p, c_size_t,
@@ -71,10 +73,12 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_bsmm.argtypes = [ctypes.c_int, POINTER(DMoETopology), ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                               c_void_p, c_void_p, c_void_p, c_void_p]
     lib.dmoe_probe_mfma_tflops.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
+    lib.dmoe_probe_mfma_sustained.argtypes = [POINTER(ctypes.c_float), POINTER(ctypes.c_float), ctypes.c_float, c_void_p,
+                                              c_void_p]
     lib.dmoe_last_error.restype = c_char_p
     for name in ("dmoe_sizes", "dmoe_topology_bind", "dmoe_topology", "dmoe_topology_static", "dmoe_forward", "dmoe_backward",
                  "dmoe_backward_accumulate", "dmoe_topology_counts_host", "dmoe_set_stage_events", "dmoe_set_tile_mode", "dmoe_bsmm_sizes",
-                 "dmoe_bsmm_topology", "dmoe_bsmm", "dmoe_probe_mfma_tflops"):
+                 "dmoe_bsmm_topology", "dmoe_bsmm", "dmoe_probe_mfma_tflops", "dmoe_probe_mfma_sustained"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -238,6 +242,15 @@ def dmoe_probe_mfma_tflops(stream=None) -> float:
     scratch = torch.zeros(64, dtype=torch.float32, device="cuda")
     _check(load_library().dmoe_probe_mfma_tflops(byref(out), _ptr(scratch), _stream(stream)))
     return out.value
+
+
+def dmoe_probe_mfma_sustained(seconds: float = 0.3, stream=None):
+    """(TFLOP/s, shader GHz) of the register-only bf16 MFMA loop after about `seconds` of sustained load (synchronises)."""
+    tf, ghz = ctypes.c_float(), ctypes.c_float()
+    scratch = torch.zeros(64, dtype=torch.float32, device="cuda")
+    _check(load_library().dmoe_probe_mfma_sustained(byref(tf), byref(ghz), float(seconds), _ptr(scratch),
+                                                    _stream(stream)))
+    return tf.value, ghz.value
 
 
 def dmoe_set_tile_mode(mode: int):

@@ -420,6 +420,19 @@ int dmoe_topology_counts_host(const dmoe_topology_t* topo, int32_t* out4, void* 
   return DMOE_OK;
 }
 
+int dmoe_debug_scratch_offset(const dmoe_config* cfg, const char* region, size_t* offset) {
+  Dims m;
+  if (int rc = check_config(cfg, &m)) return rc;
+  if (!region || !offset) return fail(DMOE_EINVAL, "NULL argument");
+  const ScratchLayout sl = scratch_layout(m);
+  const struct { const char* name; size_t off; } table[] = {
+      {"chunk_counts", sl.chunk_counts}, {"dyp", sl.dyp}, {"dh", sl.dh}, {"dxp", sl.dxp},
+      {"dweights", sl.dweights}, {"dlogits", sl.dlogits}, {"partials", sl.partials}};
+  for (const auto& t : table)
+    if (strcmp(t.name, region) == 0) { *offset = t.off; return DMOE_OK; }
+  return fail(DMOE_EINVAL, "unknown scratch region '%s'", region);
+}
+
 int dmoe_set_stage_events(void* events) {
   g_events = static_cast<hipEvent_t*>(events);
   return DMOE_OK;

@@ -54,6 +54,42 @@ __global__ void __launch_bounds__(256) mfma_peak_kernel(float* sink, int iters) 
   if (s == -1.0f) sink[0] = s;                        // never true: the products are non-negative
 }
 
+// The same loop shaped like a wave of the 256x256 tile (4 A fragments x 2 B fragments, eight accumulators, two waves
+// per SIMD), fed with pseudo-random operands whose mantissa bits change every iteration, and run long enough for the
+// power management to settle: the matrix-pipe rate the device SUSTAINS on data that toggles like real data.  Lane 0
+// of workgroup 0 brackets the loop with the shader-clock counter and the 100 MHz wall counter.
+__global__ void __launch_bounds__(512) mfma_sustained_kernel(float* sink, int iters, long long* clocks) {
+  uint32_t seed = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
+  auto next = [&]() { seed = seed * 1664525u + 1013904223u; return seed; };
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 ar[4], br[2];
+  // bf16 pairs with exponent 126..127 (magnitude 0.5..2), random sign and mantissa
+  auto rnd_pair = [&]() { const uint32_t r = next(); return (r & 0x80ff80ffu) | 0x3f003f00u | ((r >> 9) & 0x00800080u); };
+  for (int i = 0; i < 4; ++i) for (int q = 0; q < 4; ++q) ar[i][q] = rnd_pair();
+  for (int j = 0; j < 2; ++j) for (int q = 0; q < 4; ++q) br[j][q] = rnd_pair();
+  f32x16_v acc[4][2];
+  for (int i = 0; i < 4; ++i) for (int j = 0; j < 2; ++j) for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+  long long c0 = 0, w0 = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) { c0 = clock64(); w0 = wall_clock64(); }
+  for (int it = 0; it < iters; ++it) {
+    const uint32_t flip = (next() >> 8) & 0x007f007fu;          // new mantissa bits, exponents and signs stay
+    ar[it & 3][it & 3 ^ 1] ^= flip;
+    br[it & 1][(it >> 1) & 3] ^= flip;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        union { u32x4 u; bf16x8_v v; } a, b;
+        a.u = ar[i];  b.u = br[j];
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b.v, a.v, acc[i][j], 0, 0, 0);
+      }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) { clocks[0] = clock64() - c0; clocks[1] = wall_clock64() - w0; }
+  float sum = 0.0f;
+  for (int i = 0; i < 4; ++i) for (int j = 0; j < 2; ++j) sum += acc[i][j][0] + acc[i][j][15];
+  if (sum == 1.2345e-30f) sink[0] = sum;              // practically never: keeps the accumulators alive
+}
+
 }  // namespace dmoe
 
 using namespace dmoe;
@@ -186,6 +222,46 @@ int dmoe_probe_mfma_tflops(float* tflops, void* scratch4, void* stream) {
   if (err != hipSuccess || ms <= 0.0f) return fail(DMOE_ELAUNCH, "timing the probe failed: %s", hipGetErrorString(err));
   const double flops = (double)grid * 4 /* waves */ * iters * 8 /* MFMAs */ * (2.0 * 32 * 32 * 16);
   *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+  return launch_status();
+}
+
+int dmoe_probe_mfma_sustained(float* tflops, float* shader_ghz, float seconds, void* scratch64, void* stream) {
+  if (!tflops || !shader_ghz) return fail(DMOE_EINVAL, "tflops or shader_ghz is NULL");
+  if (!(seconds > 0.0f) || seconds > 5.0f) return fail(DMOE_EINVAL, "seconds must be in (0, 5]");
+  if (int rc = check_ptr(scratch64, "scratch64")) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return fail(DMOE_ELAUNCH, "hipEventCreate failed");
+  float* sink = static_cast<float*>(scratch64);
+  long long* clocks = reinterpret_cast<long long*>(static_cast<char*>(scratch64) + 16);
+  const int grid = 256, iters = 1 << 16;              // one workgroup of eight waves per CU; about 10 ms per launch
+  const double flops_per_launch = (double)grid * 8 * iters * 8 * (2.0 * 32 * 32 * 16);
+  (void)hipGetLastError();
+  // launches back to back until `seconds` have passed on the host clock; the last five are the ones timed
+  float ms = 0.0f;
+  hipError_t err = hipSuccess;
+  int launches = 0;
+  const int max_launches = (int)(seconds * 1000.0f / 5.0f) + 8;
+  double elapsed_ms = 0.0;
+  while (err == hipSuccess && launches < max_launches && elapsed_ms < seconds * 1000.0) {
+    (void)hipEventRecord(e0, s);
+    for (int i = 0; i < 5; ++i)
+      hipLaunchKernelGGL(mfma_sustained_kernel, dim3(grid), dim3(512), 0, s, sink, iters, clocks);
+    (void)hipEventRecord(e1, s);
+    err = hipEventSynchronize(e1);
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    elapsed_ms += ms;
+    launches += 5;
+  }
+  long long host_clocks[2] = {0, 0};
+  if (err == hipSuccess) err = hipMemcpy(host_clocks, clocks, sizeof(host_clocks), hipMemcpyDeviceToHost);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (err != hipSuccess || ms <= 0.0f || host_clocks[1] <= 0)
+    return fail(DMOE_ELAUNCH, "timing the sustained probe failed: %s", hipGetErrorString(err));
+  *tflops = (float)(5.0 * flops_per_launch / (ms * 1e-3) / 1e12);
+  *shader_ghz = (float)((double)host_clocks[0] / ((double)host_clocks[1] / 0.1) );   // wall counter: 100 MHz
   return launch_status();
 }
 

@@ -27,9 +27,17 @@ def _host(t):
 
 
 def _close(got, want, what):
-    scale = max(float(np.abs(want).max()), 1e-30)
-    err = float(np.abs(got - want).max()) / scale
-    assert err <= 1e-2, "%s: max relative error %.3e" % (what, err)
+    """The layer's own check: tensor-wide maximum <= 1e-2, and every 128x128 tile against its own maximum (a misplaced
+    or missing block cannot hide behind the tensor-wide figure).  Block values [nnz, 128, 128] are checked block by
+    block as a [nnz*128, 128] matrix."""
+    from tests._harness import check_values
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if got.ndim == 3:
+        got, want = got.reshape(-1, got.shape[-1]), want.reshape(-1, want.shape[-1])
+    if want.size == 0:
+        return
+    check_values(what, got, want)
 
 
 MASKS = {
