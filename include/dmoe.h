@@ -158,6 +158,14 @@ DMOE_API int dmoe_topology_counts_host(const dmoe_topology_t *topo, int32_t *out
  * [T,E] fp32; "partials"; "chunk_counts").  Host pointers; no GPU work.  Errors: DMOE_EINVAL (unknown name).       */
 DMOE_API int dmoe_debug_scratch_offset(const dmoe_config *cfg, const char *region, size_t *offset);
 
+/* Measurement aid: while `buffer` (device, 256-byte aligned, zero-filled by the caller) is non-NULL, the block-sparse
+ * product of stage `stage` (DMOE_STAGE_SDD ... DMOE_STAGE_DDTS) launched by this thread's next calls records, per work
+ * item w < bytes/40, five int64 at buffer[5w...]: the 100 MHz wall counter when the item starts, when its first
+ * operands are in LDS, when its K loop ends, when its epilogue ends, and its number of K tiles (64 of K each).
+ * Items are numbered as the launch numbers them (workgroup index plus multiples of the grid for persistent launches).
+ * NULL switches it off.  Errors: DMOE_EINVAL.                                                                    */
+DMOE_API int dmoe_debug_trace(void *buffer, size_t bytes, int stage);
+
 /* Timing helper for benchmarks: when `events` (host array of 2*DMOE_NUM_STAGES hipEvent_t, created by the
  * caller) is non-NULL, the next calls on this thread record an event before and after each stage's kernels
  * on the stream they are launched on.  Pass NULL to switch it off.  Stage numbers are DMOE_STAGE_*.           */

@@ -66,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.dmoe_set_stage_events.argtypes = [c_void_p]
     lib.dmoe_debug_scratch_offset.argtypes = [POINTER(DMoEConfig), c_char_p, POINTER(c_size_t)]
     lib.dmoe_debug_scratch_offset.restype = ctypes.c_int
+    lib.dmoe_debug_trace.argtypes = [c_void_p, c_size_t, ctypes.c_int]
+    lib.dmoe_debug_trace.restype = ctypes.c_int
     lib.dmoe_set_tile_mode.argtypes = [ctypes.c_int]
     lib.dmoe_bsmm_sizes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, POINTER(c_size_t)]
     lib.dmoe_bsmm_topology.argtypes = [c_void_p, ctypes.c_int, ctypes.c_int, c_void_p, c_size_t,

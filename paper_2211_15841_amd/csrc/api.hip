@@ -13,6 +13,8 @@ static thread_local char g_err[512] = "";
 static thread_local hipEvent_t* g_events = nullptr;
 static thread_local int g_pending = DMOE_OK;   // an error found by a launcher, reported by the next launch_status()
 static std::atomic<int> g_force_tile{0};
+static thread_local long long* g_trace = nullptr;    // dmoe_debug_trace: buffer, capacity in items, stage to trace
+static thread_local int g_trace_cap = 0, g_trace_stage = -1;
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -302,11 +304,13 @@ int dmoe_forward(const dmoe_config* cfg, const void* x, const void* w1, const vo
   ev.begin(DMOE_STAGE_SDD);
   a.dense_a = xp; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = nullptr; a.out0 = hval; a.out1 = aval;
   a.act = cfg->activation;
+  a.trace = g_trace_stage == DMOE_STAGE_SDD ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_SDD, a, s);
   ev.end(DMOE_STAGE_SDD);
 
   ev.begin(DMOE_STAGE_DSD);
   a.dense_a = nullptr; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = aval; a.out0 = yp; a.out1 = nullptr;
+  a.trace = g_trace_stage == DMOE_STAGE_DSD ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_DSD, a, s);
   ev.end(DMOE_STAGE_DSD);
 
@@ -367,24 +371,28 @@ static int backward_impl(const dmoe_config* cfg, const void* x, const void* w_ro
 
   ev.begin(DMOE_STAGE_SDDT);   // dA = dYp W2^T on the nonzero blocks, dH = dA * G with G = gelu'(H) kept by forward
   a.dense_a = dyp; a.dense_b = static_cast<const bf16_t*>(w2); a.sparse_in = hval; a.out0 = dh; a.out1 = nullptr;
+  a.trace = g_trace_stage == DMOE_STAGE_SDDT ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_SDDT, a, s);
   ev.end(DMOE_STAGE_SDDT);
 
   ev.begin(DMOE_STAGE_DSTD);   // dW2 = A^T dYp
   a.dense_a = dyp; a.dense_b = nullptr; a.sparse_in = aval; a.out0 = static_cast<bf16_t*>(dw2);
   a.accum = accumulate;
+  a.trace = g_trace_stage == DMOE_STAGE_DSTD ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_DSTD, a, s);
   a.accum = 0;
   ev.end(DMOE_STAGE_DSTD);
 
   ev.begin(DMOE_STAGE_DSDT);   // dXp = dH W1^T
   a.dense_a = nullptr; a.dense_b = static_cast<const bf16_t*>(w1); a.sparse_in = dh; a.out0 = dxp;
+  a.trace = g_trace_stage == DMOE_STAGE_DSDT ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_DSDT, a, s);
   ev.end(DMOE_STAGE_DSDT);
 
   ev.begin(DMOE_STAGE_DDTS);   // dW1 = Xp^T dH
   a.dense_a = xp; a.dense_b = nullptr; a.sparse_in = dh; a.out0 = static_cast<bf16_t*>(dw1);
   a.accum = accumulate;
+  a.trace = g_trace_stage == DMOE_STAGE_DDTS ? g_trace : nullptr;  a.trace_cap = g_trace_cap;
   launch_bsmm(OP_DDTS, a, s);
   a.accum = 0;
   ev.end(DMOE_STAGE_DDTS);
@@ -431,6 +439,15 @@ int dmoe_debug_scratch_offset(const dmoe_config* cfg, const char* region, size_t
   for (const auto& t : table)
     if (strcmp(t.name, region) == 0) { *offset = t.off; return DMOE_OK; }
   return fail(DMOE_EINVAL, "unknown scratch region '%s'", region);
+}
+
+int dmoe_debug_trace(void* buffer, size_t bytes, int stage) {
+  if (buffer && (reinterpret_cast<uintptr_t>(buffer) & 255)) return fail(DMOE_EINVAL, "trace buffer is not 256-byte aligned");
+  if (buffer && (stage < DMOE_STAGE_SDD || stage > DMOE_STAGE_DDTS)) return fail(DMOE_EINVAL, "stage %d is not a block-sparse product", stage);
+  g_trace = static_cast<long long*>(buffer);
+  g_trace_cap = buffer ? (int)(bytes / 40 > 0x7fffffff ? 0x7fffffff : bytes / 40) : 0;
+  g_trace_stage = buffer ? stage : -1;
+  return DMOE_OK;
 }
 
 int dmoe_set_stage_events(void* events) {

@@ -33,6 +33,7 @@ namespace dmoe {
 constexpr int kBlockElems = kBlock * kBlock;  // 16384 values per sparse block
 constexpr int kPatch = 32;                    // macro tiles that should run together on one XCD (one per CU)
 constexpr int kMaxGradGrid = 4096;            // cap on the grid of a weight-gradient launch (multiple of 8 * kPatch)
+constexpr int kPersistGrid = 256;             // workgroups of a persistent launch: one per CU (a multiple of 8 * kPatch)
 constexpr int kPatchSlack = 5;                // tolerated XCD imbalance, in 64ths, when the patch size is chosen
 
 struct BsParams {
@@ -61,6 +62,8 @@ struct BsParams {
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
   int ka;                  // DDS: leading dimension of dense_a
   int coo;                 // 1: SDD / SDD^T take one nonzero block per workgroup, found through row_indices
+  long long* trace;        // optional (NULL = off): per work item, four 100 MHz time stamps and the K tile count
+  int trace_cap;           // work items the trace buffer has room for
 };
 
 template <int OP> struct OpLayouts;
@@ -103,6 +106,14 @@ __device__ __forceinline__ int balanced_patch(int items, int slack) {
 //   2,1 -> 256x128 (each wave 64x64), three LDS stages;
 //   1,1 -> a single 128x128 block shared by eight waves (32x64 each), two or more workgroups per CU: half the
 //          arithmetic intensity but four times as many work items, for under-filled launches.
+// One work item of a launch: which blocks of the macro tile exist, where their operands start, how long K is.
+struct TileState {
+  bool a_ok1, b_ok1;               // the second A panel / B panel of the tile exists (the first always does)
+  int nk;                          // K tiles
+  int r0, r1, first0, first1, c0, c1, jd0;
+  int ix0, ix1, ix2;               // lane-distributed topology indices of the K loop (see refill)
+};
+
 template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
 __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm_kernel(const BsParams p) {
   constexpr int LA = OpLayouts<OP>::A, LB = OpLayouts<OP>::B;
@@ -119,6 +130,11 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   static_assert(WB == 2 || WB == 4 || WB == 8, "unsupported tile / workgroup shape");
   constexpr bool kSparseOut = OP == OP_SDD || OP == OP_SDDT;
   constexpr bool kRowMajor = kSparseOut || OP == OP_DSD || OP == OP_DSDT;   // items enumerate block rows
+  // The 256x256 tiles of the token-row products run as a persistent, software-pipelined loop over the items of a
+  // workgroup (see the end of the kernel); everything else takes one item at a time.
+  constexpr bool kPipe = kRowMajor && PA == 2 && PB == 2 && NS == 2 && NW == 8;
+  constexpr int kEpRows = MI >= 2 ? 64 : 32;        // rows of the wave's tile that pass through its staging tile at a time
+  constexpr int kEpBytes = kEpRows * 128;           // per wave: 8 KB (4 KB for the 32-row waves)
   extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A slabs, B slabs]
 
   const int tid = threadIdx.x;
@@ -136,95 +152,86 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   constexpr int UD = kColsInB ? PA : PB;                        // d-blocks per unit
   const int ncu = (hb + UC - 1) / UC, nju = (db + UD - 1) / UD;
 
-  // One workgroup, one tile for the products whose rows are tokens.  The weight-gradient launches are capped at
-  // kMaxGradGrid workgroups, each taking the items wgi, wgi + gridDim, ... (heaviest first, so the strided lists
-  // cost about the same): the launch that the device-side choice leaves idle then costs a few microseconds instead
-  // of one dispatch per tile (40-50 us for the 30 000 small tiles of the larger configurations; the same loop on the
-  // token-row products changed nothing).  Under skewed routing a workgroup that drew a tile of the hot expert still
-  // takes its share of light ones afterwards (+6 % on those two kernels, lost in the noise of the whole step).
-  auto tile = [&](const int wgi) {
   // ---- which tile ------------------------------------------------------------------------------------------
   // Items are numbered so that 4 consecutive "major" indices (row units, or column units for the weight
   // gradients) times all "minor" indices form a run: id = (major / 4 * nminor + minor) * 4 + major % 4.
-  int major, minor, P;
-  {
-    const bool coo = kSparseOut && PA * PB == 1 && p.coo;
-    const int nminor = coo ? 1 : kSparseOut ? ncu : nju;
-    if constexpr (kRowMajor) {
-      const int majors = coo ? p.counts[2] : PA == 2 ? p.group_offsets[p.E] : p.counts[1];
-      P = p.patch > 0 ? p.patch : balanced_patch((majors + 3) / 4 * 4 * nminor, -p.patch);
-    } else {
-      P = p.sched[1];                               // 1 or 16, chosen with the routing in hand (offsets_kernel)
-    }
-    const int item = patch_item(wgi, P);
-    const int run = item / (4 * nminor), rem = item % (4 * nminor);
-    major = run * 4 + (rem & 3);
-    minor = rem >> 2;
-  }
-  bool a_ok[2] = {true, false}, b_ok[2] = {true, false};
-  int nk = 0;
-  int r0 = 0, r1 = 0, first0 = 0, first1 = 0, c0 = 0, c1 = 0, jd0 = 0;
+  // Returns false when the item does not exist for this routing (grids are sized for upper bounds).
+  const bool coo_launch = kSparseOut && PA * PB == 1 && p.coo;
+  const int nminor = coo_launch ? 1 : kSparseOut ? ncu : nju;
+  int majors_live = 0, patch = 1;
   if constexpr (kRowMajor) {
-    bool is_coo = false;
-    if constexpr (kSparseOut && PA * PB == 1) is_coo = p.coo;
-    if (is_coo) {
-      // A general mask may have any number of blocks in a row; the per-block row index of the hybrid encoding lets
-      // SDD give every nonzero block its own workgroup without searching the row offsets (Section 5.1.3).
-      if (major >= p.counts[2]) return;
-      first0 = first1 = major;
-      r0 = r1 = p.row_indices[major];
-      c0 = c1 = p.column_indices[major];
-      nk = d / BK;
-    } else {
-      if constexpr (PA == 2) {
-        if (major >= p.group_offsets[p.E]) return;
-        const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
-        r0 = rg >> 1;
-        a_ok[1] = rg & 1;
-      } else {
-        if (major >= p.counts[1]) return;
-        r0 = major;
-      }
-      r1 = a_ok[1] ? r0 + 1 : r0;
-      first0 = p.row_offsets[r0];
-      first1 = p.row_offsets[r1];
-      const int nblk = p.row_offsets[r0 + 1] - first0;
-      if constexpr (kSparseOut) {
-        if (PB * minor >= nblk) return;
-        b_ok[1] = PB == 2 && 2 * minor + 1 < nblk;
-        first0 += PB * minor;                         // block (r0, c0); (r0, c1) is the next one
-        first1 += PB * minor;
-        c0 = p.column_indices[first0];
-        c1 = b_ok[1] ? p.column_indices[first0 + 1] : c0;
-        nk = d / BK;
-      } else {
-        jd0 = PB * minor;
-        b_ok[1] = PB == 2 && jd0 + 1 < db;
-        nk = kSub * nblk;
-      }
-    }
+    majors_live = coo_launch ? p.counts[2] : PA == 2 ? p.group_offsets[p.E] : p.counts[1];
+    patch = p.patch > 0 ? p.patch : balanced_patch((majors_live + 3) / 4 * 4 * nminor, -p.patch);
   } else {
-    if (major >= p.E * ncu) return;
-    // heaviest experts first; with patches, consecutive experts go to consecutive XCDs, so every second group of
-    // eight is taken in reverse (the XCD that got the heaviest of one group gets the lightest of the next)
-    int rank = major / ncu;
-    if (P > 1 && (rank & 8) && (rank | 7) < p.E) rank = (rank & ~7) | (7 - (rank & 7));
-    const int e = p.expert_order[rank];
-    const int cu = major % ncu;
-    jd0 = UD * minor;
-    c0 = e * hb + UC * cu;
-    const bool second_col = UC == 2 && 2 * cu + 1 < hb;
-    const bool second_d = UD == 2 && jd0 + 1 < db;
-    c1 = second_col ? c0 + 1 : c0;
-    first0 = p.column_offsets_t[c0];
-    first1 = p.column_offsets_t[c1];
-    nk = kSub * (p.column_offsets_t[c0 + 1] - first0);
-    // The rows of an expert beyond its token count are padding (Section 5.2): zero in both operands of a weight
-    // gradient, so K tiles that lie entirely in the padding of the last block are skipped.
-    if (p.tokens_per_expert) nk = min(nk, (p.tokens_per_expert[e] + BK - 1) / BK);
-    if constexpr (OP == OP_DSTD) { a_ok[1] = second_col;  b_ok[1] = second_d; }
-    else                         { a_ok[1] = second_d;    b_ok[1] = second_col; }
+    patch = p.sched[1];                             // 1 or 16, chosen with the routing in hand (offsets_kernel)
   }
+  auto decode = [&](const int wgi, TileState& t) -> bool {
+    const int item = patch_item(wgi, patch);
+    const int run = item / (4 * nminor), rem = item % (4 * nminor);
+    const int major = run * 4 + (rem & 3), minor = rem >> 2;
+    t.a_ok1 = false;  t.b_ok1 = false;
+    t.nk = 0;  t.r0 = t.r1 = t.first0 = t.first1 = t.c0 = t.c1 = t.jd0 = 0;
+    t.ix0 = t.ix1 = t.ix2 = 0;
+    if constexpr (kRowMajor) {
+      if (major >= majors_live) return false;
+      if (coo_launch) {
+        // A general mask may have any number of blocks in a row; the per-block row index of the hybrid encoding lets
+        // SDD give every nonzero block its own workgroup without searching the row offsets (Section 5.1.3).
+        t.first0 = t.first1 = major;
+        t.r0 = t.r1 = p.row_indices[major];
+        t.c0 = t.c1 = p.column_indices[major];
+        t.nk = d / BK;
+        return true;
+      }
+      if constexpr (PA == 2) {
+        const int rg = p.row_group[major];            // first block-row * 2 + (group has a second row)
+        t.r0 = rg >> 1;
+        t.a_ok1 = rg & 1;
+      } else {
+        t.r0 = major;
+      }
+      t.r1 = t.a_ok1 ? t.r0 + 1 : t.r0;
+      t.first0 = p.row_offsets[t.r0];
+      t.first1 = p.row_offsets[t.r1];
+      const int nblk = p.row_offsets[t.r0 + 1] - t.first0;
+      if constexpr (kSparseOut) {
+        if (PB * minor >= nblk) return false;
+        t.b_ok1 = PB == 2 && 2 * minor + 1 < nblk;
+        t.first0 += PB * minor;                       // block (r0, c0); (r0, c1) is the next one
+        t.first1 += PB * minor;
+        t.c0 = p.column_indices[t.first0];
+        t.c1 = t.b_ok1 ? p.column_indices[t.first0 + 1] : t.c0;
+        t.nk = d / BK;
+      } else {
+        t.jd0 = PB * minor;
+        t.b_ok1 = PB == 2 && t.jd0 + 1 < db;
+        t.nk = kSub * nblk;
+      }
+      return true;
+    } else {
+      if (major >= p.E * ncu) return false;
+      // heaviest experts first; with patches, consecutive experts go to consecutive XCDs, so every second group of
+      // eight is taken in reverse (the XCD that got the heaviest of one group gets the lightest of the next)
+      int rank = major / ncu;
+      if (patch > 1 && (rank & 8) && (rank | 7) < p.E) rank = (rank & ~7) | (7 - (rank & 7));
+      const int e = p.expert_order[rank];
+      const int cu = major % ncu;
+      t.jd0 = UD * minor;
+      t.c0 = e * hb + UC * cu;
+      const bool second_col = UC == 2 && 2 * cu + 1 < hb;
+      const bool second_d = UD == 2 && t.jd0 + 1 < db;
+      t.c1 = second_col ? t.c0 + 1 : t.c0;
+      t.first0 = p.column_offsets_t[t.c0];
+      t.first1 = p.column_offsets_t[t.c1];
+      t.nk = kSub * (p.column_offsets_t[t.c0 + 1] - t.first0);
+      // The rows of an expert beyond its token count are padding (Section 5.2): zero in both operands of a weight
+      // gradient, so K tiles that lie entirely in the padding of the last block are skipped.
+      if (p.tokens_per_expert) t.nk = min(t.nk, (p.tokens_per_expert[e] + BK - 1) / BK);
+      if constexpr (OP == OP_DSTD) { t.a_ok1 = second_col;  t.b_ok1 = second_d; }
+      else                         { t.a_ok1 = second_d;    t.b_ok1 = second_col; }
+      return true;
+    }
+  };
 
   // ---- per-K-tile slab base pointers (wave-uniform) --------------------------------------------------------
   const bf16_t *a0, *a1, *b0, *b1;
@@ -241,75 +248,74 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // kept lane-distributed in registers, 64 blocks at a time (lane i holds the values of block 64 c + i), and picked
   // out with v_readlane: an index load inside the loop would put its latency between the barrier and the loads
   // that the barrier releases, with every wave waiting.
-  int ix0 = 0, ix1 = 0, ix2 = 0;
-  auto refill = [&](int kb0) {
-    const int n = (nk + kSub - 1) / kSub - kb0;     // blocks left from kb0 on (the last one may be cut short)
+  auto refill = [&](TileState& t, int kb0) {
+    const int n = (t.nk + kSub - 1) / kSub - kb0;   // blocks left from kb0 on (the last one may be cut short)
     if (lane < n) {
       if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-        ix0 = p.column_indices[first0 + kb0 + lane];
+        t.ix0 = p.column_indices[t.first0 + kb0 + lane];
       } else if constexpr (OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS) {
-        ix0 = p.block_offsets_t[first0 + kb0 + lane];
-        ix1 = p.block_offsets_t[first1 + kb0 + lane];
-        ix2 = p.row_indices_t[first0 + kb0 + lane];
+        t.ix0 = p.block_offsets_t[t.first0 + kb0 + lane];
+        t.ix1 = p.block_offsets_t[t.first1 + kb0 + lane];
+        t.ix2 = p.row_indices_t[t.first0 + kb0 + lane];
       }
     }
     // consume the values here, so that the wait for these loads is placed inside this rarely taken branch and not
     // in front of the v_readlane of every iteration
-    asm volatile("" : "+v"(ix0), "+v"(ix1), "+v"(ix2));
+    asm volatile("" : "+v"(t.ix0), "+v"(t.ix1), "+v"(t.ix2));
   };
-  auto slab_ptrs = [&](int kt) {
+  auto slab_ptrs = [&](TileState& t, int kt) {
     if constexpr (OP == OP_SDD) {
-      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * BK;
-      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * BK;
-      b0 = p.dense_b + (size_t)kt * BK * ldw + (size_t)c0 * kBlock;
-      b1 = p.dense_b + (size_t)kt * BK * ldw + (size_t)c1 * kBlock;
+      a0 = p.dense_a + (size_t)t.r0 * kBlock * d + kt * BK;
+      a1 = p.dense_a + (size_t)t.r1 * kBlock * d + kt * BK;
+      b0 = p.dense_b + (size_t)kt * BK * ldw + (size_t)t.c0 * kBlock;
+      b1 = p.dense_b + (size_t)kt * BK * ldw + (size_t)t.c1 * kBlock;
     } else if constexpr (OP == OP_SDDT) {
-      a0 = p.dense_a + (size_t)r0 * kBlock * d + kt * BK;
-      a1 = p.dense_a + (size_t)r1 * kBlock * d + kt * BK;
-      b0 = p.dense_b + (size_t)c0 * kBlock * d + kt * BK;
-      b1 = p.dense_b + (size_t)c1 * kBlock * d + kt * BK;
+      a0 = p.dense_a + (size_t)t.r0 * kBlock * d + kt * BK;
+      a1 = p.dense_a + (size_t)t.r1 * kBlock * d + kt * BK;
+      b0 = p.dense_b + (size_t)t.c0 * kBlock * d + kt * BK;
+      b1 = p.dense_b + (size_t)t.c1 * kBlock * d + kt * BK;
     } else if constexpr (OP == OP_DSD) {
       const int kb = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(kb);
-      const int col = __builtin_amdgcn_readlane(ix0, kb & 63);
-      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
-      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
-      b0 = p.dense_b + ((size_t)col * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
-      b1 = b0 + (b_ok[1] ? kBlock : 0);
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
+      a0 = p.sparse_in + (size_t)(t.first0 + kb) * kBlockElems + half * BK;
+      a1 = p.sparse_in + (size_t)(t.first1 + kb) * kBlockElems + half * BK;
+      b0 = p.dense_b + ((size_t)col * kBlock + half * BK) * d + (size_t)t.jd0 * kBlock;
+      b1 = b0 + (t.b_ok1 ? kBlock : 0);
     } else if constexpr (OP == OP_DSDT) {
       const int kb = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(kb);
-      const int col = __builtin_amdgcn_readlane(ix0, kb & 63);
-      a0 = p.sparse_in + (size_t)(first0 + kb) * kBlockElems + half * BK;
-      a1 = p.sparse_in + (size_t)(first1 + kb) * kBlockElems + half * BK;
-      b0 = p.dense_b + (size_t)jd0 * kBlock * ldw + (size_t)col * kBlock + half * BK;
-      b1 = b0 + (b_ok[1] ? (size_t)kBlock * ldw : 0);
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
+      a0 = p.sparse_in + (size_t)(t.first0 + kb) * kBlockElems + half * BK;
+      a1 = p.sparse_in + (size_t)(t.first1 + kb) * kBlockElems + half * BK;
+      b0 = p.dense_b + (size_t)t.jd0 * kBlock * ldw + (size_t)col * kBlock + half * BK;
+      b1 = b0 + (t.b_ok1 ? (size_t)kBlock * ldw : 0);
     } else if constexpr (OP == OP_DSTD) {
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(i);
-      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
-      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
       a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
       a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
-      b0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
-      b1 = b0 + (b_ok[1] ? kBlock : 0);
+      b0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)t.jd0 * kBlock;
+      b1 = b0 + (t.b_ok1 ? kBlock : 0);
     } else if constexpr (OP == OP_DDS) {
       // Y = X S: for the blocks (row, c) of column c, in the order of the transposed lists, X[:, row] times the block
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(i);
-      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
-      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
-      a0 = p.dense_a + (size_t)jd0 * kBlock * p.ka + (size_t)row * kBlock + half * BK;
-      a1 = a0 + (a_ok[1] ? (size_t)kBlock * p.ka : 0);
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
+      a0 = p.dense_a + (size_t)t.jd0 * kBlock * p.ka + (size_t)row * kBlock + half * BK;
+      a1 = a0 + (t.a_ok1 ? (size_t)kBlock * p.ka : 0);
       b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
       b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
     } else {  // OP_DDTS
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(i);
-      const int blk0 = __builtin_amdgcn_readlane(ix0, i & 63), blk1 = __builtin_amdgcn_readlane(ix1, i & 63);
-      const int row = __builtin_amdgcn_readlane(ix2, i & 63);
-      a0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)jd0 * kBlock;
-      a1 = a0 + (a_ok[1] ? kBlock : 0);
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
+      a0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)t.jd0 * kBlock;
+      a1 = a0 + (t.a_ok1 ? kBlock : 0);
       b0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
       b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
     }
@@ -320,8 +326,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // A load takes the slab's base pointer from scalar registers (it is the same for the whole wave) and a per-lane
   // 32-bit byte offset from one vector register: against a 64-bit address per lane this halves the vector-register
   // reads of every load and removes the 64-bit vector additions that built the addresses inside the MFMA stream
-  // (-11 % cycles per K tile in a dense probe of this loop).  Offsets stay below 2^27 bytes (127 rows of at most
-  // 2^19 elements).
+  // (-11 % cycles per K tile in a dense probe of this loop).  Offsets stay below 2^32 bytes (127 rows of fewer than
+  // 2^24 elements).
   uint32_t oa[kCpw], ob[kCpw];
 #pragma unroll
   for (int i = 0; i < kCpw; ++i) {
@@ -357,41 +363,279 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   };
 
   f32x16_v acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[i][jj][q] = 0.0f;
-
-  const bool mine = a_ok[pm] && b_ok[pn];          // this wave's part of the tile exists
-  // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
-  // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
-  // t has landed; near the end of K, when fewer tiles are in flight, the wait is for everything.
-  auto multiply = [&](const char* sa, const char* sb, int ks) {
-    bf16x8_v af[MI], bf[2];
-#pragma unroll
-    for (int i = 0; i < MI; ++i) af[i] = load_frag<LA, BK>(sa, arow0 + 32 * i, ks, lane);
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj) bf[jj] = load_frag<LB, BK>(sb, hn * 64 + 32 * jj, ks, lane);
-    // Operands swapped on purpose: the MFMA "row" index runs over n and the "column" index over m, so each
-    // lane ends up with four consecutive n of one output row and can store them as one 8-byte word.
+  auto clear_acc = [&]() {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj)
-        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[jj], af[i], acc[i][jj], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[i][jj][q] = 0.0f;
   };
+
+  struct Frags { bf16x8_v a[MI], b[2]; };
+  auto read_frags = [&](Frags& f, const char* sa, const char* sb, int ks) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) f.a[i] = load_frag<LA, BK>(sa, arow0 + 32 * i, ks, lane);
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) f.b[jj] = load_frag<LB, BK>(sb, hn * 64 + 32 * jj, ks, lane);
+  };
+  // Operands swapped on purpose: the MFMA "row" index runs over n and the "column" index over m, so each
+  // lane ends up with four consecutive n of one output row and can store them as one 8-byte word.
+  auto mfma_frags = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[jj], f.a[i], acc[i][jj], 0, 0, 0);
+  };
+  auto multiply = [&](const char* sa, const char* sb, int ks) {
+    Frags f;
+    read_frags(f, sa, sb, ks);
+    mfma_frags(f);
+  };
+
+  // ---- epilogue.  Lane l, accumulator register 4q+u of tile (i, jj) is
+  //      C[arow0 + 32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn).
+  // Written straight from there, every store instruction would touch 32 rows with 16 bytes each; instead the
+  // wave's tile is rounded to bf16 into a wave-private LDS staging tile (128-byte rows, chunk-swizzled like a
+  // KC slab), kEpRows rows at a time, and written out as whole 128-byte row segments, 1 KB per store instruction.
+  // `ep`: this wave's staging tile (kEpBytes; the accumulating form of the weight gradients uses 4 KB per 32 rows).
+  auto epilogue = [&](const TileState& t, char* ep) {
+    bf16_t* out;
+    size_t ldo;
+    size_t blk = 0;
+    if constexpr (kSparseOut) {
+      blk = (size_t)((pm ? t.first1 : t.first0) + pn) * kBlockElems + (size_t)arow0 * kBlock + hn * 64;
+      out = p.out0 + blk;  ldo = kBlock;
+    } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
+      out = p.out0 + ((size_t)(pm ? t.r1 : t.r0) * kBlock + arow0) * d + (size_t)(t.jd0 + pn) * kBlock + hn * 64;  ldo = d;
+    } else if constexpr (OP == OP_DSTD) {
+      out = p.out0 + ((size_t)(pm ? t.c1 : t.c0) * kBlock + arow0) * d + (size_t)(t.jd0 + pn) * kBlock + hn * 64;  ldo = d;
+    } else {
+      out = p.out0 + ((size_t)(t.jd0 + pm) * kBlock + arow0) * ldw + (size_t)(pn ? t.c1 : t.c0) * kBlock + hn * 64;  ldo = ldw;
+    }
+    if constexpr (!kRowMajor) {
+      if (p.accum) {
+        // fp32 accumulation: out0 is an fp32 matrix of the same shape.  The staging tile holds 32 columns at a time
+        // (128-byte rows again), so every load and store below covers whole 128-byte row segments.  The tile belongs
+        // to this workgroup alone, so a plain read-modify-write is enough.
+        float* outf = reinterpret_cast<float*>(p.out0) + (out - p.out0);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              float4 v;
+              v.x = acc[i][jj][4 * q + 0];  v.y = acc[i][jj][4 * q + 1];
+              v.z = acc[i][jj][4 * q + 2];  v.w = acc[i][jj][4 * q + 3];
+              *reinterpret_cast<float4*>(ep + kc_offset<64>(32 * i + (lane & 31), 2 * q + (lane >> 5))) = v;
+            }
+#pragma unroll 2                               // not fully: the hoisted addresses would cost registers in every variant
+          for (int it = 0; it < 4 * MI; ++it) {
+            const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+            const float4 v = *reinterpret_cast<const float4*>(ep + kc_offset<64>(row, chunk));
+            float4* g = reinterpret_cast<float4*>(outf + (size_t)row * ldo + 32 * jj + chunk * 4);
+            float4 o = *g;
+            o.x += v.x;  o.y += v.y;  o.z += v.z;  o.w += v.w;
+            *g = o;
+          }
+        }
+        return;
+      }
+    }
+    constexpr int CH = kEpRows / 32;                             // 32-row MFMA tiles per pass through the staging tile
+    auto slot = [&](int il, int jj, int q) -> uint2* {          // this lane's 4 values of tile (il, jj) of the pass, quad q
+      return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * il + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
+    };
+    auto flush = [&](bf16_t* dst) {                             // staging tile -> global, row-contiguous
+#pragma unroll
+      for (int it = 0; it < 4 * CH; ++it) {
+        const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4*>(ep + kc_offset<64>(row, chunk));
+        *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
+      }
+    };
+    // SDD writes two tensors from the same fp32 values: out1 <- A = gelu(H) = H Phi(H) for the second layer, and
+    // out0 <- G = gelu'(H) = Phi(H) + H phi(H), which is all the backward pass needs of H (one evaluation of Phi and
+    // phi serves both, and SDD^T then only multiplies).
+    // (The form of the activation, ACT, is a template parameter: a run-time choice inside this loop made the compiler
+    // evaluate both forms for every element, and one copy of the loop per form cost the 256x256 tile its registers.)
+#pragma unroll
+    for (int c = 0; c < MI / CH; ++c) {
+      const size_t row_off = (size_t)(32 * CH * c) * ldo;
+      if (OP == OP_SDDT && !p.plain) {                          // global -> staging tile: G = gelu'(H)
+        const bf16_t* src = p.sparse_in + blk + row_off;
+#pragma unroll
+        for (int it = 0; it < 4 * CH; ++it) {
+          const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+          *reinterpret_cast<uint4*>(ep + kc_offset<64>(row, chunk)) =
+              *reinterpret_cast<const uint4*>(src + (size_t)row * ldo + chunk * 8);
+        }
+      }
+#pragma unroll
+      for (int il = 0; il < CH; ++il) {
+        const int i = CH * c + il;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float v[4] = {acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1], acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]};
+            uint2 ov;
+            if (OP == OP_SDDT && !p.plain) {
+              const uint2 gv = *slot(il, jj, q);
+              ov.x = pack_bf16(v[0] * bf16_lo(gv.x), v[1] * bf16_hi(gv.x));
+              ov.y = pack_bf16(v[2] * bf16_lo(gv.y), v[3] * bf16_hi(gv.y));
+            } else if (OP == OP_SDD && !p.plain) {
+              float g[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                float cdf, pdf;
+                if constexpr (ACT == 1) tanh_gelu_cdf_pdf(v[u], cdf, pdf);
+                else                    normal_cdf_pdf(v[u], cdf, pdf);
+                g[u] = fmaf(v[u], pdf, cdf);
+                v[u] *= cdf;
+                acc[i][jj][4 * q + u] = v[u];          // keep A for the second pass through the staging tile
+              }
+              ov.x = pack_bf16(g[0], g[1]);  ov.y = pack_bf16(g[2], g[3]);
+            } else {
+              ov.x = pack_bf16(v[0], v[1]);  ov.y = pack_bf16(v[2], v[3]);
+            }
+            *slot(il, jj, q) = ov;
+          }
+      }
+      flush(out + row_off);
+      if (OP == OP_SDD && !p.plain) {
+#pragma unroll
+        for (int il = 0; il < CH; ++il) {
+          const int i = CH * c + il;
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              uint2 av;
+              av.x = pack_bf16(acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1]);
+              av.y = pack_bf16(acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]);
+              *slot(il, jj, q) = av;
+            }
+        }
+        flush(p.out1 + blk + row_off);
+      }
+    }
+  };
+
+  // Optional trace (measurement aid): wave 0 of the workgroup stamps the 100 MHz wall counter at four points of an item.
+  auto stamp = [&](int wgi, int k, int nk) {
+    if (p.trace && tid == 0 && wgi < p.trace_cap) {
+      p.trace[(size_t)wgi * 5 + k] = wall_clock64();
+      if (k == 0) p.trace[(size_t)wgi * 5 + 4] = nk;
+    }
+  };
+  if constexpr (kPipe) {
+    // ---- persistent, software-pipelined loop over this workgroup's items (256x256 tiles of the token-row products)
+    // One workgroup per CU walks the items blockIdx, blockIdx + grid, ...  Two things are overlapped that a
+    // tile-per-workgroup launch leaves exposed (together about a fifth of a tile's time when K is 16-24 K tiles):
+    //  * the next item's set-up (a chain of dependent index loads) and the loads of its first K tile are issued during
+    //    the last K tile of the current item and land while its epilogue runs.  The two LDS stages alternate across
+    //    items: the first K tile of the next item goes to the stage that the last K tile of this one does not use,
+    //    and the epilogue's staging tiles live in the stage that it does use;
+    //  * inside an item, the MFMA operands of K step s+1 are read from LDS before the MFMAs of step s are issued
+    //    (two fragment sets), and the last K step of a K tile is multiplied after the barrier of the next K tile, behind
+    //    the LDS reads of its first step, so the matrix pipe has work across the barrier.
+    // live items (the grid's upper bound may be larger), rounded up to whole patches on every XCD: workgroup -> item
+    // is a permutation inside blocks of 8 * patch indices (patch is a power of two <= 32), so whole blocks are walked
+    const int items = ((majors_live + 3) / 4 * 4 * nminor + 8 * kPatch - 1) / (8 * kPatch) * (8 * kPatch);
+    TileState cur, nxt;
+    int wgi = blockIdx.x;
+    bool have = false;
+    for (; wgi < items; wgi += gridDim.x)
+      if (decode(wgi, cur)) { have = true; break; }
+    int s0 = 0;                                                  // LDS stage of the current item's first K tile
+    if (have) {
+      slab_ptrs(cur, 0);
+      issue_loads(s0, 0);
+      issue_loads(s0, 1);
+    }
+    while (have) {
+      bool have_next = false;
+      int nwgi = wgi + gridDim.x;
+      for (; nwgi < items; nwgi += gridDim.x)
+        if (decode(nwgi, nxt)) { have_next = true; break; }
+      const int nk = cur.nk;
+      const bool mine = (pm == 0 || cur.a_ok1) && (pn == 0 || cur.b_ok1);   // this wave's part of the tile exists
+      clear_acc();
+      Frags f0, f1;
+      stamp(wgi, 0, nk);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();              // K tile 0 visible; every wave is done with the previous item's staging tiles
+      stamp(wgi, 1, nk);
+      {
+        const char* st = lds + s0 * kStageBytes;
+        if (mine) read_frags(f0, st + pm * kPanelBytes, st + (PA + pn) * kPanelBytes, 0);
+      }
+      for (int kt = 0; kt < nk; ++kt) {
+        const int stage = (s0 + kt) & 1;
+        const char* sa = lds + stage * kStageBytes + pm * kPanelBytes;
+        const char* sb = lds + stage * kStageBytes + (PA + pn) * kPanelBytes;
+        // what the other stage receives while this K tile is multiplied: the next K tile, or the next item's first
+        const bool more = kt + 1 < nk;
+        const bool feed = more || have_next;
+        if (more) slab_ptrs(cur, kt + 1);
+        else if (have_next) slab_ptrs(nxt, 0);
+        if (feed) issue_loads(stage ^ 1, 0);
+        if (mine) {
+          if (kt > 0) mfma_frags(f1);                            // K step 3 of the previous K tile
+          read_frags(f1, sa, sb, 1);
+        }
+        if (feed) issue_loads(stage ^ 1, 1);
+        if (mine) {
+          mfma_frags(f0);
+          read_frags(f0, sa, sb, 2);
+          mfma_frags(f1);
+          read_frags(f1, sa, sb, 3);
+          mfma_frags(f0);
+        }
+        if (more) {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();          // K tile kt+1 visible; everyone has read all of K tile kt
+          if (mine) {
+            const char* st = lds + (stage ^ 1) * kStageBytes;
+            read_frags(f0, st + pm * kPanelBytes, st + (PA + pn) * kPanelBytes, 0);
+          }
+        }
+      }
+      if (mine) mfma_frags(f1);
+      const int last_stage = (s0 + nk - 1) & 1;
+      stamp(wgi, 2, nk);
+      __syncthreads();              // every wave has read the last K tile: its stage is free for the staging tiles
+      if (mine) epilogue(cur, lds + last_stage * kStageBytes + wave * kEpBytes);
+      stamp(wgi, 3, nk);
+      s0 = last_stage ^ 1;
+      cur = nxt;
+      wgi = nwgi;
+      have = have_next;
+    }
+  } else {
+  auto tile = [&](const int wgi) {
+  TileState t;
+  if (!decode(wgi, t)) return;
+  const int nk = t.nk;
+  clear_acc();
+  stamp(wgi, 0, nk);
+  const bool mine = (pm == 0 || t.a_ok1) && (pn == 0 || t.b_ok1);          // this wave's part of the tile exists
+  // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
+  // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
+  // t has landed; near the end of K, when fewer tiles are in flight, the wait is for everything.
   // The 128x128 tile spends about 130 cycles of an iteration on MFMAs and the rest waiting for memory, so hiding
   // the loads behind the arithmetic of the same iteration buys nothing there.  Its two stages are used the other
   // way round: a stage is refilled (with tile kt + 2) as soon as every wave has multiplied it, one barrier later,
   // which keeps two tiles in flight instead of one (-9 % on the weight gradients under skewed routing, -1...4 % on a step).
   if constexpr (PA * PB <= 2 && NS == 2) {
-    for (int t = 0; t < 2; ++t) {
-      if (t < nk) {
-        slab_ptrs(t);
-        issue_loads(t, 0);
-        issue_loads(t, 1);
+    for (int kt = 0; kt < 2; ++kt) {
+      if (kt < nk) {
+        slab_ptrs(t, kt);
+        issue_loads(kt, 0);
+        issue_loads(kt, 1);
       }
     }
     for (int kt = 0; kt < nk; ++kt) {
@@ -406,18 +650,18 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       }
       if (kt + 2 < nk) {
         __syncthreads();                           // everyone is done reading this stage
-        slab_ptrs(kt + 2);
+        slab_ptrs(t, kt + 2);
         issue_loads(kt & 1, 0);
         issue_loads(kt & 1, 1);
       }
     }
   } else {
 #pragma unroll
-  for (int t = 0; t < NS - 1; ++t) {
-    if (t < nk) {
-      slab_ptrs(t);
-      issue_loads(t, 0);
-      issue_loads(t, 1);
+  for (int kt = 0; kt < NS - 1; ++kt) {
+    if (kt < nk) {
+      slab_ptrs(t, kt);
+      issue_loads(kt, 0);
+      issue_loads(kt, 1);
     }
   }
   for (int kt = 0; kt < nk; ++kt) {
@@ -426,7 +670,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     __syncthreads();                               // tile kt visible to all; everyone is done with tile kt-1
     const bool more = kt + NS - 1 < nk;
     const int next_stage = (kt + NS - 1) % NS;
-    if (more) slab_ptrs(kt + NS - 1);
+    if (more) slab_ptrs(t, kt + NS - 1);
     const char* sa = lds + (kt % NS) * kStageBytes + pm * kPanelBytes;
     const char* sb = lds + (kt % NS) * kStageBytes + (PA + pn) * kPanelBytes;
     // The loads of the next tile are spread over the first two K steps instead of being issued in one burst: a
@@ -438,127 +682,13 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     }
   }
   }
+  stamp(wgi, 2, nk);
   __syncthreads();                                 // every wave is done with the operand stages: LDS is free
+  if (tid == 0 && !mine) stamp(wgi, 3, nk);
   if (!mine) return;
-
-  // ---- epilogue.  Lane l, accumulator register 4q+u of tile (i, jj) is
-  //      C[arow0 + 32 i + l%32][hn*64 + 32 jj + 8 q + 4 (l/32) + u]  of this wave's 128x128 block (pm, pn).
-  // Written straight from there, every store instruction would touch 32 rows with 16 bytes each; instead the
-  // wave's (32 MI) x 64 tile is rounded to bf16 into a wave-private LDS tile (128-byte rows, chunk-swizzled like a
-  // KC slab) and written out as whole 128-byte row segments, 1 KB per store instruction.
-  char* ep = lds + wave * (MI * 4096);
-  bf16_t* out;
-  size_t ldo;
-  size_t blk = 0;
-  if constexpr (kSparseOut) {
-    blk = (size_t)((pm ? first1 : first0) + pn) * kBlockElems + (size_t)arow0 * kBlock + hn * 64;
-    out = p.out0 + blk;  ldo = kBlock;
-  } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
-    out = p.out0 + ((size_t)(pm ? r1 : r0) * kBlock + arow0) * d + (size_t)(jd0 + pn) * kBlock + hn * 64;  ldo = d;
-  } else if constexpr (OP == OP_DSTD) {
-    out = p.out0 + ((size_t)(pm ? c1 : c0) * kBlock + arow0) * d + (size_t)(jd0 + pn) * kBlock + hn * 64;  ldo = d;
-  } else {
-    out = p.out0 + ((size_t)(jd0 + pm) * kBlock + arow0) * ldw + (size_t)(pn ? c1 : c0) * kBlock + hn * 64;  ldo = ldw;
-  }
-  if constexpr (!kRowMajor) {
-    if (p.accum) {
-      // fp32 accumulation: out0 is an fp32 matrix of the same shape.  The staging tile holds 32 columns at a time
-      // (128-byte rows again), so every load and store below covers whole 128-byte row segments.  The tile belongs
-      // to this workgroup alone, so a plain read-modify-write is enough.
-      float* outf = reinterpret_cast<float*>(p.out0) + (out - p.out0);
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float4 v;
-            v.x = acc[i][jj][4 * q + 0];  v.y = acc[i][jj][4 * q + 1];
-            v.z = acc[i][jj][4 * q + 2];  v.w = acc[i][jj][4 * q + 3];
-            *reinterpret_cast<float4*>(ep + kc_offset<64>(32 * i + (lane & 31), 2 * q + (lane >> 5))) = v;
-          }
-#pragma unroll 2                               // not fully: the hoisted addresses would cost registers in every variant
-        for (int it = 0; it < 4 * MI; ++it) {
-          const int row = 8 * it + (lane >> 3), chunk = lane & 7;
-          const float4 v = *reinterpret_cast<const float4*>(ep + kc_offset<64>(row, chunk));
-          float4* g = reinterpret_cast<float4*>(outf + (size_t)row * ldo + 32 * jj + chunk * 4);
-          float4 o = *g;
-          o.x += v.x;  o.y += v.y;  o.z += v.z;  o.w += v.w;
-          *g = o;
-        }
-      }
-      return;
-    }
-  }
-  auto slot = [&](int i, int jj, int q) -> uint2* {          // this lane's 4 values of tile (i, jj), quad q
-    return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * i + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
-  };
-  auto flush = [&](bf16_t* dst) {                             // staging tile -> global, row-contiguous
-#pragma unroll
-    for (int it = 0; it < 4 * MI; ++it) {
-      const int row = 8 * it + (lane >> 3), chunk = lane & 7;
-      const uint4 v = *reinterpret_cast<const uint4*>(ep + kc_offset<64>(row, chunk));
-      *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
-    }
-  };
-  if (OP == OP_SDDT && !p.plain) {                            // global -> staging tile: G = gelu'(H)
-    const bf16_t* src = p.sparse_in + blk;
-#pragma unroll
-    for (int it = 0; it < 4 * MI; ++it) {
-      const int row = 8 * it + (lane >> 3), chunk = lane & 7;
-      *reinterpret_cast<uint4*>(ep + kc_offset<64>(row, chunk)) =
-          *reinterpret_cast<const uint4*>(src + (size_t)row * ldo + chunk * 8);
-    }
-  }
-  // SDD writes two tensors from the same fp32 values: out1 <- A = gelu(H) = H Phi(H) for the second layer, and
-  // out0 <- G = gelu'(H) = Phi(H) + H phi(H), which is all the backward pass needs of H (one evaluation of Phi and
-  // phi serves both, and SDD^T then only multiplies).
-  // (The form of the activation, ACT, is a template parameter: a run-time choice inside this loop made the compiler
-  // evaluate both forms for every element, and one copy of the loop per form cost the 256x256 tile its registers.)
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float v[4] = {acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1], acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]};
-        uint2 ov;
-        if (OP == OP_SDDT && !p.plain) {
-          const uint2 gv = *slot(i, jj, q);
-          ov.x = pack_bf16(v[0] * bf16_lo(gv.x), v[1] * bf16_hi(gv.x));
-          ov.y = pack_bf16(v[2] * bf16_lo(gv.y), v[3] * bf16_hi(gv.y));
-        } else if (OP == OP_SDD && !p.plain) {
-          float g[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            float c, d0;
-            if constexpr (ACT == 1) tanh_gelu_cdf_pdf(v[u], c, d0);
-            else                    normal_cdf_pdf(v[u], c, d0);
-            g[u] = fmaf(v[u], d0, c);
-            v[u] *= c;
-            acc[i][jj][4 * q + u] = v[u];          // keep A for the second pass through the staging tile
-          }
-          ov.x = pack_bf16(g[0], g[1]);  ov.y = pack_bf16(g[2], g[3]);
-        } else {
-          ov.x = pack_bf16(v[0], v[1]);  ov.y = pack_bf16(v[2], v[3]);
-        }
-        *slot(i, jj, q) = ov;
-      }
-  flush(out);
-  if (OP == OP_SDD && !p.plain) {
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          uint2 av;
-          av.x = pack_bf16(acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1]);
-          av.y = pack_bf16(acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]);
-          *slot(i, jj, q) = av;
-        }
-    flush(p.out1 + blk);
-  }
+  // the accumulating form of the weight gradients stages 32 columns of fp32 per 32 rows: 4 KB per 32-row tile
+  epilogue(t, lds + wave * (MI * 4096));
+  stamp(wgi, 3, nk);
   };   // tile
 
   if constexpr (kRowMajor) {
@@ -567,10 +697,16 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     // Both tile shapes are launched for the weight gradients; the routing decides on the device which one works.
     const int want_small = p.force_tile ? (p.force_tile == 1) : p.sched[0];
     if (want_small != (PA * PB == 1 ? 1 : 0)) return;
+    // The weight-gradient launches are capped at kMaxGradGrid workgroups, each taking the items wgi, wgi + gridDim,
+    // ... (heaviest first, so the strided lists cost about the same): the launch that the device-side choice leaves
+    // idle then costs a few microseconds instead of one dispatch per tile (40-50 us for the 30 000 small tiles of the
+    // larger configurations).  Under skewed routing a workgroup that drew a tile of the hot expert still takes its
+    // share of light ones afterwards.
     for (int wgi = blockIdx.x; wgi < p.items; wgi += gridDim.x) {
       tile(wgi);
       __syncthreads();                               // the epilogue's staging tiles are the next item's stages
     }
+  }
   }
 }
 
@@ -596,6 +732,9 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
   q.items = grid;
   constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS;
   if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
+  // the 256x256 tiles of the token-row products run as a persistent loop: one workgroup per CU (128 KB of LDS each)
+  constexpr bool pipe = !grad && PA == 2 && PB == 2 && NS == 2 && NW == 8;
+  if (pipe && grid > kPersistGrid) grid = kPersistGrid;
   hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>), dim3(grid), dim3(NW * 64), kLds, s, q);
 }
 
@@ -670,6 +809,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.accum = a.accum;
   p.ka = a.ka;
   p.coo = a.coo;
+  p.trace = a.trace;  p.trace_cap = a.trace_cap;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless

@@ -95,6 +95,8 @@ struct BsArgs {
   int act;                 // SDD's fused activation: 0 exact (erf) GELU, 1 tanh form
   int coo;                 // 1 (general masks): SDD / SDD^T enumerate the nonzero blocks through row_indices
   int nnz;                 // ... and this many of them
+  long long* trace;        // optional per-item time stamps of this launch (NULL = off), room for trace_cap items
+  int trace_cap;
   const bf16_t* dense_a;   // Xp / dYp           (SDD, SDDT: lhs;  DSTD, DDTS: the dense operand)
   const bf16_t* dense_b;   // W1 / W2            (SDD, DSD, SDDT, DSDT: rhs)
   const bf16_t* sparse_in; // block values read  (DSD, DSTD, DSDT, DDTS: sparse operand; SDDT: G = gelu'(H))
