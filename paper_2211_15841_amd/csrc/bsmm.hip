@@ -622,6 +622,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   const int nk = t.nk;
   clear_acc();
   stamp(wgi, 0, nk);
+  stamp(wgi, 1, nk);
   const bool mine = (pm == 0 || t.a_ok1) && (pn == 0 || t.b_ok1);          // this wave's part of the tile exists
   // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
   // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
