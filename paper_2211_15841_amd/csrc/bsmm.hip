@@ -444,6 +444,58 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
         return;
       }
     }
+    if constexpr (OP == OP_SDDT) {
+      if (!p.plain) {
+        // dH = dA * G with G = gelu'(H) kept by the forward pass.  G comes in by direct-to-LDS loads, 32 rows at a time
+        // and two steps ahead of its use, straight into the wave's staging tile in the tile's own swizzled layout; the
+        // product is formed in place and written out as whole 128-byte row segments.  No vector register carries G,
+        // and the counted waits below let the stores of earlier steps stay in flight (loads and stores retire in
+        // order): [G(i+1)] or [stores(i-1), G(i+1)] may be outstanding when G(i) is needed.
+        constexpr int NH = kEpRows / 32;                         // 4 KB halves of the staging tile
+        static_assert((MI == 4 && NH == 2) || (MI == 1 && NH == 1), "wait counts below are written for these shapes");
+        const bf16_t* gsrc = p.sparse_in + blk;
+        const uint32_t ep_lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)ep);
+        const uint32_t off_even = 2u * dma_lane_offset<KC, 64>(0, lane, kBlock);
+        const uint32_t off_odd = 2u * (dma_lane_offset<KC, 64>(1, lane, kBlock) - 8 * kBlock);
+        auto fetch_g = [&](int i) {
+#pragma unroll
+          for (int ch = 0; ch < 4; ++ch)
+            dma16(gsrc + (32 * i + 8 * ch) * kBlock, (ch & 1) ? off_odd : off_even, ep_lds + (i % NH) * 4096 + 1024 * ch);
+        };
+        fetch_g(0);
+        if constexpr (MI > 1) fetch_g(1);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const int il = i % NH;
+          if constexpr (MI == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          else if (i == 0 || i == MI - 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+          else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              uint2* sl = reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * il + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
+              const uint2 gv = *sl;
+              uint2 ov;
+              ov.x = pack_bf16(acc[i][jj][4 * q + 0] * bf16_lo(gv.x), acc[i][jj][4 * q + 1] * bf16_hi(gv.x));
+              ov.y = pack_bf16(acc[i][jj][4 * q + 2] * bf16_lo(gv.y), acc[i][jj][4 * q + 3] * bf16_hi(gv.y));
+              *sl = ov;
+            }
+          bf16_t* dst = out + (size_t)(32 * i) * ldo;
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            const int row = 8 * it + (lane >> 3), chunk = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4*>(ep + kc_offset<64>(32 * il + row, chunk));
+            *reinterpret_cast<uint4*>(dst + (size_t)row * ldo + chunk * 8) = v;
+          }
+          if (i + NH < MI) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // the reads of this half are done before it is refilled
+            fetch_g(i + NH);
+          }
+        }
+        return;
+      }
+    }
     constexpr int CH = kEpRows / 32;                             // 32-row MFMA tiles per pass through the staging tile
     auto slot = [&](int il, int jj, int q) -> uint2* {          // this lane's 4 values of tile (il, jj) of the pass, quad q
       return reinterpret_cast<uint2*>(ep + kc_offset<64>(32 * il + (lane & 31), 4 * jj + q) + 8 * (lane >> 5));
