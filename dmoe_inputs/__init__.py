@@ -31,6 +31,8 @@ class Config:
     seed: int = 0
     block: int = BLOCK
     activation: int = 0          # 0: exact (erf) GELU
+    expert_capacity: int = 0     # > 0: the token-dropping variant, at most this many assignments per expert
+    pad_to_capacity: int = 0     # 1: every expert owns the capacity's worth of rows
 
     def as_dict(self):
         return asdict(self)
@@ -104,6 +106,8 @@ def make_inputs(cfg: Config, with_grad: bool = True) -> dict:
     return out
 
 
-def small_config(name="case", T=300, d=128, h=256, E=5, k=2, normalize_topk=0, zipf_s=0.0, seed=7) -> Config:
+def small_config(name="case", T=300, d=128, h=256, E=5, k=2, normalize_topk=0, zipf_s=0.0, seed=7,
+                 expert_capacity=0, pad_to_capacity=0) -> Config:
     """Helper for tests: an arbitrary small configuration."""
-    return Config(name, T, d, h, E, k, normalize_topk=normalize_topk, zipf_s=zipf_s, seed=seed)
+    return Config(name, T, d, h, E, k, normalize_topk=normalize_topk, zipf_s=zipf_s, seed=seed,
+                  expert_capacity=expert_capacity, pad_to_capacity=pad_to_capacity)

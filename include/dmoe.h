@@ -62,6 +62,14 @@ typedef struct {
                               0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3))) */
   int32_t normalize_topk;  /* 0: confidence = softmax probability of the chosen expert (Section 2.1);
                               1: that, divided by the sum over the token's k chosen experts */
+  int32_t expert_capacity; /* 0: dropless (the dMoE of Section 4: every assignment is computed).  > 0: the
+                              token-dropping MoE of Section 2.2 on the same kernels: an expert keeps the first
+                              expert_capacity assignments routed to it, in ascending flat index f; the others are
+                              dropped (row_of[f] = -1, no contribution to y, no gradient through them).  The caller
+                              computes it, e.g. as num_tokens*top_k/num_experts * capacity_factor (Section 2.2) */
+  int32_t pad_to_capacity; /* with expert_capacity > 0 only.  0: a group is padded to the next multiple of 128 rows
+                              as in the dropless layer; 1: every expert owns ceil(expert_capacity/128)*128 rows,
+                              unused capacity being zero rows (the fixed shape of Section 2.2 and Figure 2)  */
 } dmoe_config;
 
 /* Routing result + block-sparse topology, all in device memory (views into one caller-owned allocation,

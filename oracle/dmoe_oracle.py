@@ -157,6 +157,59 @@ def permutation(expert_idx: np.ndarray, num_experts: int, block: int = BLOCK):
     return n, offsets.astype(np.int32), row_of, token_of
 
 
+# ----------------------------------------------------------------------------- token dropping (Section 2.2)
+def expert_capacity(num_tokens: int, num_experts: int, capacity_factor: float, top_k: int = 1) -> int:
+    """Section 2.2: expert_capacity = num_tokens / num_experts x capacity_factor, the number of assignments an
+    expert may take.  With top_k choices per token there are num_tokens*top_k assignments to share out (reading:
+    the paper writes the top-1 case).  Rounded down, at least 1."""
+    return max(1, int(math.floor(num_tokens * top_k / num_experts * capacity_factor)))
+
+
+def capacity_keep_mask(expert_idx: np.ndarray, num_experts: int, capacity: int) -> np.ndarray:
+    """bool [T,k]: assignment f = t*k + s is kept iff fewer than `capacity` assignments with a smaller f went to the
+    same expert (Section 2.2: tokens beyond an expert's capacity are dropped; reading: in flat order, the first
+    ones stay).  capacity <= 0 keeps everything (the dropless layer)."""
+    flat = np.asarray(expert_idx, dtype=np.int64).reshape(-1)
+    keep = np.ones(flat.size, dtype=bool)
+    if capacity > 0:
+        taken = np.zeros(num_experts, dtype=np.int64)
+        for f in range(flat.size):
+            e = flat[f]
+            keep[f] = taken[e] < capacity
+            taken[e] += 1
+    return keep.reshape(np.asarray(expert_idx).shape)
+
+
+def permutation_capacity(expert_idx: np.ndarray, num_experts: int, capacity: int, pad_to_capacity: bool = False,
+                         block: int = BLOCK):
+    """permutation() for the token-dropping layer: an expert's group holds its kept assignments only (ascending f);
+    dropped assignments have row_of = -1.  A group is padded to the next multiple of `block`, or, with
+    pad_to_capacity, every expert owns ceil(capacity/block)*block rows (unused capacity is padding, Section 2.2).
+
+    Returns tokens_per_expert (kept) [E], padded_offsets [E+1], row_of [T*k], token_of [P]."""
+    flat = np.asarray(expert_idx, dtype=np.int64).reshape(-1)
+    keep = capacity_keep_mask(expert_idx, num_experts, capacity).reshape(-1)
+    n = np.zeros(num_experts, dtype=np.int32)
+    members = []
+    for e in range(num_experts):
+        S_e = np.flatnonzero((flat == e) & keep)
+        members.append(S_e)
+        n[e] = S_e.size
+    if pad_to_capacity:
+        padded = np.full(num_experts, ((capacity + block - 1) // block) * block, dtype=np.int64)
+    else:
+        padded = -(-n.astype(np.int64) // block) * block           # next multiple of the block
+    offsets = np.zeros(num_experts + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(padded)
+    row_of = np.full(flat.size, -1, dtype=np.int32)
+    token_of = np.full(int(offsets[-1]), -1, dtype=np.int32)
+    for e in range(num_experts):
+        for j, f in enumerate(members[e]):
+            row_of[f] = offsets[e] + j
+            token_of[offsets[e] + j] = f
+    return n, offsets.astype(np.int32), row_of, token_of
+
+
 # ----------------------------------------------------------------------------- topology (Fig. 3C, 5.1.3, 5.1.4)
 def block_mask(padded_offsets: np.ndarray, hb: int, block: int = BLOCK) -> np.ndarray:
     """Dense 0/1 map of nonzero blocks, R x (E*hb): block-row r of expert e is nonzero exactly on that
@@ -247,10 +300,16 @@ def _members(expert_idx: np.ndarray, e: int) -> np.ndarray:
     return np.flatnonzero(np.asarray(expert_idx).reshape(-1) == e)
 
 
-def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep: bool = False, activation: int = 0):
+def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep: bool = False, activation: int = 0,
+            keep_mask=None):
     """y[t] = sum_s weights[t,s] * FFN_{e(t,s)}(x[t]),  FFN_e(v) = gelu(v W1_e) W2_e   (Sections 2.3-2.4, Fig. 6).
 
+    keep_mask (bool [T,k], optional): the token-dropping layer of Section 2.2 -- assignments whose entry is False
+    are dropped: they reach no expert and add nothing to y.
+
     Returns y float64 [T,d]; with keep=True also the per-expert intermediates for backward()."""
+    if keep_mask is not None:
+        expert_idx = np.where(np.asarray(keep_mask, dtype=bool), expert_idx, -1)      # -1 is no expert's group
     T, d = x_bits.shape
     k = expert_idx.shape[1]
     E = w1_bits.shape[1] // ffn_hidden
@@ -277,8 +336,11 @@ def forward(x_bits, w1_bits, w2_bits, expert_idx, weights, ffn_hidden: int, keep
 
 
 def backward(x_bits, wr_bits, w1_bits, w2_bits, dy_bits, expert_idx, weights, probs, ffn_hidden: int,
-             normalize_topk: int, activation: int = 0):
+             normalize_topk: int, activation: int = 0, keep_mask=None):
     """Gradients of  L = <dy, y>  with the expert assignments held constant.
+
+    keep_mask: as in forward().  A dropped assignment's confidence does not appear in y, so its dweights entry is
+    zero; the confidences themselves (and their renormalisation over the k slots) are those of the router.
 
     Returns dx [T,d], dw_router [d,E], dw1 [d,E*h], dw2 [E*h,d] (float64), and dweights [T,k]."""
     T, d = x_bits.shape
@@ -289,7 +351,8 @@ def backward(x_bits, wr_bits, w1_bits, w2_bits, dy_bits, expert_idx, weights, pr
     wr = widen_bf16(wr_bits)
     dy = widen_bf16(dy_bits)
     w_flat = np.asarray(weights, dtype=np.float64).reshape(-1)
-    _, saved = forward(x_bits, w1_bits, w2_bits, expert_idx, weights, h, keep=True, activation=activation)
+    _, saved = forward(x_bits, w1_bits, w2_bits, expert_idx, weights, h, keep=True, activation=activation,
+                       keep_mask=keep_mask)
 
     dx = np.zeros((T, d))
     dw1 = np.zeros((d, E * h))

@@ -20,7 +20,8 @@ class DMoEError(RuntimeError):
 
 class DMoEConfig(ctypes.Structure):
     _fields_ = [("num_tokens", c_int32), ("d_model", c_int32), ("ffn_hidden", c_int32), ("num_experts", c_int32),
-                ("top_k", c_int32), ("block", c_int32), ("activation", c_int32), ("normalize_topk", c_int32)]
+                ("top_k", c_int32), ("block", c_int32), ("activation", c_int32), ("normalize_topk", c_int32),
+                ("expert_capacity", c_int32), ("pad_to_capacity", c_int32)]
 
 
 _TOPO_FIELDS = ["expert_idx", "weights", "logits", "tokens_per_expert", "padded_offsets", "row_of", "token_of",
@@ -271,10 +272,11 @@ class Workspace:
     GUARD_BYTE = 0xA5
 
     def __init__(self, num_tokens, d_model, ffn_hidden, num_experts, top_k, normalize_topk=0, device="cuda:0",
-                 activation=0, guard_bytes=0):
+                 activation=0, guard_bytes=0, expert_capacity=0, pad_to_capacity=0):
         """guard_bytes > 0 (tests): every buffer the library writes sits between two guard zones of that many bytes
         holding a fixed pattern; check_guards() then tells whether any kernel wrote outside its buffer."""
-        self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, activation, normalize_topk)
+        self.cfg = DMoEConfig(num_tokens, d_model, ffn_hidden, num_experts, top_k, 128, activation, normalize_topk,
+                              expert_capacity, pad_to_capacity)
         self.device = torch.device(device)
         self.sizes = dmoe_sizes(self.cfg)
         self.guard_bytes = (int(guard_bytes) + 255) // 256 * 256

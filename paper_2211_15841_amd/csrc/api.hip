@@ -50,6 +50,9 @@ static int check_config(const dmoe_config* c, Dims* out) {
   if (c->top_k < 1 || c->top_k > kMaxTopK || c->top_k > c->num_experts) return fail(DMOE_EINVAL, "top_k must be in [1, min(num_experts, %d)] (got %d)", kMaxTopK, c->top_k);
   if (c->activation != 0 && c->activation != 1) return fail(DMOE_EINVAL, "activation must be 0 (exact GELU) or 1 (tanh form)");
   if (c->normalize_topk != 0 && c->normalize_topk != 1) return fail(DMOE_EINVAL, "normalize_topk must be 0 or 1");
+  if (c->expert_capacity < 0) return fail(DMOE_EINVAL, "expert_capacity must be >= 0 (got %d)", c->expert_capacity);
+  if (c->pad_to_capacity != 0 && c->pad_to_capacity != 1) return fail(DMOE_EINVAL, "pad_to_capacity must be 0 or 1");
+  if (c->pad_to_capacity && c->expert_capacity == 0) return fail(DMOE_EINVAL, "pad_to_capacity needs expert_capacity > 0");
   const long long F = (long long)c->num_tokens * c->top_k;
   if (F >= (1ll << 24)) return fail(DMOE_EINVAL, "num_tokens*top_k must be below 2^24 (got %lld)", F);
   const long long wcols = (long long)c->num_experts * c->ffn_hidden;
@@ -58,8 +61,15 @@ static int check_config(const dmoe_config* c, Dims* out) {
   m.T = c->num_tokens; m.d = c->d_model; m.h = c->ffn_hidden; m.E = c->num_experts; m.k = c->top_k;
   m.hb = m.h / kBlock; m.db = m.d / kBlock; m.F = (int)F;
   // sum_e ceil(n_e/128)*128 <= F + 127*min(E, F), and it is a multiple of 128
-  const long long nonempty = m.E < F ? m.E : F;
+  long long nonempty = m.E < F ? m.E : F;
   long long pm = ((F + 127 * nonempty) / kBlock) * kBlock;
+  if (c->expert_capacity > 0) {
+    // token dropping: no expert owns more than its capacity, rounded up to whole blocks
+    const long long rows_cap = ((long long)c->expert_capacity + kBlock - 1) / kBlock * kBlock;
+    if (c->pad_to_capacity) { pm = m.E * rows_cap;  nonempty = m.E; }
+    else if (m.E * rows_cap < pm) pm = m.E * rows_cap;
+    if (pm >= (1ll << 30)) return fail(DMOE_EINVAL, "num_experts*expert_capacity too large");
+  }
   if (pm / kBlock * m.hb >= (1ll << 27)) return fail(DMOE_EINVAL, "too many nonzero blocks");
   m.p_max = (int)pm; m.r_max = m.p_max / kBlock; m.nnz_max = m.r_max * m.hb;
   m.g_max = (int)((m.r_max + nonempty + 1) / 2);   // sum_e ceil(rows_e / 2)

@@ -33,6 +33,7 @@ __global__ void __launch_bounds__(256) weighted_scatter_kernel(const bf16_t* __r
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int s = 0; s < k; ++s) {
       const int row = row_of[t * k + s];
+      if (row < 0) continue;                       // a dropped assignment contributes nothing (Section 2.2)
       const float w = weights[t * k + s];
       const uint4 v = reinterpret_cast<const uint4*>(yp + (size_t)row * d)[c];
       acc[0] = fmaf(w, bf16_lo(v.x), acc[0]); acc[1] = fmaf(w, bf16_hi(v.x), acc[1]);
@@ -93,6 +94,7 @@ __global__ void __launch_bounds__(256) bwd_gather_kernel(const bf16_t* __restric
 template <int G>
 __global__ void __launch_bounds__(256) dlogits_kernel(const float* __restrict__ logits, const int32_t* __restrict__ expert_idx,
                                                       const float* __restrict__ weights, const float* __restrict__ dweights,
+                                                      const int32_t* __restrict__ row_of,
                                                       float* __restrict__ dlogits, int T, int E, int k, int normalize) {
   const int tid = threadIdx.x;
   const int sub = tid % G;
@@ -118,7 +120,7 @@ __global__ void __launch_bounds__(256) dlogits_kernel(const float* __restrict__ 
     sel[s] = -1; dsel[s] = 0.0f;
     if (s < k) {
       sel[s] = expert_idx[tt * k + s];
-      dsel[s] = dweights[tt * k + s];
+      dsel[s] = row_of[tt * k + s] < 0 ? 0.0f : dweights[tt * k + s];   // a dropped assignment has no gradient
       dot_dw_w = fmaf(dsel[s], weights[tt * k + s], dot_dw_w);
       Z += __expf(lg[sel[s]] - m) * inv;
     }
@@ -249,7 +251,7 @@ __global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       g[it][s] = make_uint4(0, 0, 0, 0);
-      if (s < k) g[it][s] = *reinterpret_cast<const uint4*>(dxp + (size_t)rows[it][s] * d + i0 + c8);
+      if (s < k && rows[it][s] >= 0) g[it][s] = *reinterpret_cast<const uint4*>(dxp + (size_t)rows[it][s] * d + i0 + c8);
     }
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
@@ -267,7 +269,7 @@ __global__ void __launch_bounds__(256) dx_mfma_kernel(const bf16_t* __restrict__
     if (t < T) {
       for (int s = 2; s < k; ++s) {
         const int row = row_of[(size_t)t * k + s];
-        add(*reinterpret_cast<const uint4*>(dxp + (size_t)row * d + i0 + c8));
+        if (row >= 0) add(*reinterpret_cast<const uint4*>(dxp + (size_t)row * d + i0 + c8));
       }
       uint4 o;
       o.x = pack_bf16(v[0], v[1]);  o.y = pack_bf16(v[2], v[3]);
@@ -418,7 +420,7 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
 #define DMOE_DL_CASE(G)                                                                                        \
   case G:                                                                                                      \
     hipLaunchKernelGGL(dlogits_kernel<G>, dim3((T + 256 / G - 1) / (256 / G)), dim3(256), 0, s, t.logits,      \
-                       t.expert_idx, t.weights, dweights, dlogits, T, E, k, c.normalize_topk);                 \
+                       t.expert_idx, t.weights, dweights, t.row_of, dlogits, T, E, k, c.normalize_topk);       \
     break;
   switch (g) {
     DMOE_DL_CASE(1)

@@ -253,7 +253,8 @@ __global__ void __launch_bounds__(256) chunk_hist_kernel(const int32_t* __restri
 // tokens_per_expert, padded_offsets (rows per expert = ceil(n_e/128)*128, Section 5.2), counts and expert_order.
 constexpr int kOffsetsThreads = 1024;          // threads of the one workgroup: up to 1024 / E lanes per expert
 __global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __restrict__ chunk_counts, int nchunks, int E, int hb,
-                                                              int db, int32_t* __restrict__ sched,
+                                                              int db, int capacity, int pad_to_capacity,
+                                                              int32_t* __restrict__ sched,
                                                        int32_t* __restrict__ tokens_per_expert,
                                                        int32_t* __restrict__ padded_offsets, int32_t* __restrict__ counts,
                                                        int32_t* __restrict__ expert_order,
@@ -292,8 +293,11 @@ __global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __res
   }
   __syncthreads();
   if (tid >= E) n = 0;                      // threads 0..E-1 (part 0, ex == tid) own expert tid from here on
+  // Token dropping (Section 2.2): an expert keeps at most `capacity` assignments (the first ones in flat order, see
+  // rank_kernel); with pad_to_capacity every expert owns the capacity's worth of rows whatever its load.
+  if (capacity > 0) n = min(n, capacity);
   if (tid < E) tokens_per_expert[tid] = n;
-  const int padded = ((n + kBlock - 1) / kBlock) * kBlock;
+  const int padded = ((((pad_to_capacity && tid < E) ? capacity : n) + kBlock - 1) / kBlock) * kBlock;
   const bool slot = tid < kMaxExperts;      // the per-expert arrays have kMaxExperts entries
   if (slot) {
     n_s[tid] = n;
@@ -349,7 +353,7 @@ __global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __res
 
 __global__ void __launch_bounds__(256) rank_kernel(const int32_t* __restrict__ expert_idx, int F, int E, int nbits,
                                                    int nchunks, const int32_t* __restrict__ chunk_base,
-                                                   const int32_t* __restrict__ padded_offsets,
+                                                   const int32_t* __restrict__ padded_offsets, int capacity,
                                                    int32_t* __restrict__ row_of, int32_t* __restrict__ token_of) {
   __shared__ int cnt_all[4 * kMaxExperts];
   const int wave = threadIdx.x >> 6;
@@ -358,7 +362,12 @@ __global__ void __launch_bounds__(256) rank_kernel(const int32_t* __restrict__ e
   if (chunk >= nchunks) return;
   const int32_t* base = chunk_base + (size_t)chunk * E;
   chunk_ranks(expert_idx, F, chunk, E, nbits, cnt, [&](int f, int e, int r) {
-    const int row = padded_offsets[e] + base[e] + r;
+    const int rank = base[e] + r;                          // position of f among the assignments of expert e
+    if (capacity > 0 && rank >= capacity) {                // over capacity: dropped (Section 2.2)
+      row_of[f] = -1;
+      return;
+    }
+    const int row = padded_offsets[e] + rank;
     row_of[f] = row;
     token_of[row] = f;
   });
@@ -480,10 +489,10 @@ void launch_sort(const dmoe_config& c, const dmoe_topology_t& t, int32_t* chunk_
   hipLaunchKernelGGL(chunk_hist_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
                      chunk_counts);
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kOffsetsThreads), 0, s, chunk_counts, nchunks, E, hb,
-                     c.d_model / kBlock, t.sched, t.tokens_per_expert,
+                     c.d_model / kBlock, c.expert_capacity, c.pad_to_capacity, t.sched, t.tokens_per_expert,
                      t.padded_offsets, t.counts, t.expert_order, t.group_offsets);
   hipLaunchKernelGGL(rank_kernel, dim3((nchunks + 3) / 4), dim3(256), 0, s, t.expert_idx, F, E, nbits, nchunks,
-                     chunk_counts, t.padded_offsets, t.row_of, t.token_of);
+                     chunk_counts, t.padded_offsets, c.expert_capacity, t.row_of, t.token_of);
 }
 
 void launch_make_topology(const dmoe_config& c, const dmoe_topology_t& t, int p_max, int nnz_max, hipStream_t s) {

@@ -25,7 +25,8 @@ def bf16_to_np(t: torch.Tensor) -> np.ndarray:
 def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
     # every buffer the library writes lies between guard zones, checked after the calls: no kernel may write outside
     ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk,
-                      activation=cfg.activation, guard_bytes=GUARD_BYTES)
+                      activation=cfg.activation, guard_bytes=GUARD_BYTES, expert_capacity=cfg.expert_capacity,
+                      pad_to_capacity=cfg.pad_to_capacity)
     if poison:      # unwritten regions must not look like zeros (empty experts, padding rows)
         for t in (ws.topology_mem, ws.saved, ws.scratch):
             t.fill_(0xFF)
@@ -53,7 +54,11 @@ def run_gpu(cfg: Config, inp: dict, backward: bool = True, poison: bool = True):
 
 def run_oracle_indices(cfg: Config, inp: dict):
     logits, idx, w, p = orc.route(inp["x"], inp["w_router"], inp["router_bias"], cfg.top_k, cfg.normalize_topk)
-    n, off, row_of, token_of = orc.permutation(idx, cfg.num_experts)
+    if cfg.expert_capacity > 0:                       # the token-dropping variant (Section 2.2)
+        n, off, row_of, token_of = orc.permutation_capacity(idx, cfg.num_experts, cfg.expert_capacity,
+                                                            bool(cfg.pad_to_capacity))
+    else:
+        n, off, row_of, token_of = orc.permutation(idx, cfg.num_experts)
     topo = orc.topology(off, cfg.ffn_hidden)
     ref = dict(topo, logits=logits, expert_idx=idx, weights=w, probs=p, tokens_per_expert=n, padded_offsets=off,
                row_of=row_of, token_of=token_of)
@@ -118,9 +123,12 @@ def full_parity(cfg: Config, inp: dict | None = None):
     ref = run_oracle_indices(cfg, inp)
     check_indices(gpu["topo"], ref)
     h = cfg.ffn_hidden
-    y = orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], h, activation=cfg.activation)
+    keep = (orc.capacity_keep_mask(ref["expert_idx"], cfg.num_experts, cfg.expert_capacity)
+            if cfg.expert_capacity > 0 else None)
+    y = orc.forward(inp["x"], inp["w1"], inp["w2"], ref["expert_idx"], ref["weights"], h, activation=cfg.activation,
+                    keep_mask=keep)
     g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], ref["expert_idx"], ref["weights"],
-                     ref["probs"], h, cfg.normalize_topk, activation=cfg.activation)
+                     ref["probs"], h, cfg.normalize_topk, activation=cfg.activation, keep_mask=keep)
     errs = {"y": check_values("y", gpu["y"], y)}
     for name in ("dx", "dw1", "dw2"):
         errs[name] = check_values(name, gpu[name], g[name])

@@ -11,8 +11,8 @@ import paper_2211_15841_amd as dm
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _cfg(T=1024, d=256, h=1024, E=4, k=1, block=128, act=0, norm=0):
-    return dm.DMoEConfig(T, d, h, E, k, block, act, norm)
+def _cfg(T=1024, d=256, h=1024, E=4, k=1, block=128, act=0, norm=0, cap=0, pad=0):
+    return dm.DMoEConfig(T, d, h, E, k, block, act, norm, cap, pad)
 
 
 def test_library_exports_every_declared_symbol():
@@ -37,10 +37,23 @@ def test_sizes_follow_the_documented_bounds():
     assert s2["P_max"] == 3 * 128
 
 
+def test_sizes_with_an_expert_capacity():
+    """Token dropping (Section 2.2): no expert owns more rows than its capacity rounded up to whole blocks; with padding
+    to capacity every expert owns exactly that many."""
+    free = dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64))
+    assert free["P_max"] == (8192 + 127 * 64) // 128 * 128
+    assert dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64, cap=128))["P_max"] == 64 * 128
+    assert dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64, cap=128, pad=1))["P_max"] == 64 * 128
+    assert dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64, cap=192, pad=1))["P_max"] == 64 * 256
+    assert dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64, cap=100000))["P_max"] == free["P_max"]
+    assert dm.dmoe_sizes(_cfg(T=8192, d=512, h=2048, E=64, cap=100))["nnz_max"] == 64 * 16
+
+
 @pytest.mark.parametrize("kw,frag", [
     (dict(block=64), "block"), (dict(d=200), "d_model"), (dict(h=100), "ffn_hidden"), (dict(E=0), "num_experts"),
     (dict(E=257), "num_experts"), (dict(k=0), "top_k"), (dict(k=5, E=4), "top_k"), (dict(k=9, E=16), "top_k"),
     (dict(T=0), "num_tokens"), (dict(act=2), "activation"), (dict(norm=2), "normalize_topk"),
+    (dict(cap=-1), "expert_capacity"), (dict(pad=2, cap=4), "pad_to_capacity"), (dict(pad=1), "pad_to_capacity"),
 ])
 def test_invalid_configurations_are_rejected(kw, frag):
     with pytest.raises(dm.DMoEError) as ei:

@@ -8,6 +8,7 @@ import pytest
 from oracle import dmoe_oracle as orc
 from tests import test_oracle_indices as ti
 from tests import test_oracle_values as tv
+from tests import test_oracle_capacity as tc
 
 MUTATIONS = {
     "gelu_forgets_sqrt2": ("return 0.5 * v * (1.0 + _erf(v / math.sqrt(2.0)))", "return 0.5 * v * (1.0 + _erf(v))"),
@@ -37,6 +38,14 @@ MUTATIONS = {
     "dweights_sign": ("dwt[S_e] = np.einsum(\"ij,ij->i\", dy[tok], O_e)", "dwt[S_e] = -np.einsum(\"ij,ij->i\", dy[tok], O_e)"),
     "renormalisation_gradient_drops_mean": ("dsel = (dwt - (dwt * w).sum(axis=1, keepdims=True)) / Z", "dsel = dwt / Z"),
     "softmax_jacobian_drops_projection": ("dlogits = p * (dp - (dp * p).sum(axis=1, keepdims=True))", "dlogits = p * dp"),
+    "capacity_keeps_the_last_assignments": ("for f in range(flat.size):\n            e = flat[f]\n            keep[f]",
+                                            "for f in reversed(range(flat.size)):\n            e = flat[f]\n            keep[f]"),
+    "capacity_off_by_one": ("keep[f] = taken[e] < capacity", "keep[f] = taken[e] <= capacity"),
+    "capacity_equation_ignores_the_factor": ("num_tokens * top_k / num_experts * capacity_factor", "num_tokens * top_k / num_experts"),
+    "pad_to_capacity_pads_to_the_load": ("padded = np.full(num_experts, ((capacity + block - 1) // block) * block, dtype=np.int64)",
+                                         "padded = -(-n.astype(np.int64) // block) * block"),
+    "dropped_assignments_are_computed_anyway": ("expert_idx = np.where(np.asarray(keep_mask, dtype=bool), expert_idx, -1)",
+                                                "expert_idx = expert_idx"),
     "dw_router_transposed_operand": ("dw_router = x.T @ dlogits", "dw_router = (dlogits.T @ x).T * 0 + x.T @ dlogits[::-1]"),
 }
 
@@ -60,6 +69,10 @@ def _pins():
         lambda: tv.test_backward_equals_torch_autograd_on_dense_formulation(tv.CASES[1]),
         lambda: tv.test_backward_equals_torch_autograd_on_dense_formulation(tv.CASES[2]),
         lambda: tv.test_top1_with_normalised_weight_gives_router_no_gradient(),
+        lambda: tc.test_capacity_equation_values(),
+        lambda: tc.test_keep_mask_and_permutation_invariants(tc.CASES[1]),
+        lambda: tc.test_forward_equals_gated_dense_brute_force(tc.CASES[0]),
+        lambda: tc.test_backward_equals_torch_autograd_on_gated_dense_formulation(tc.CASES[1]),
     ]
 
 
