@@ -104,7 +104,8 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
     to_dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
     x, wr, w1, w2, dy = (to_dev(inp[k]) for k in ("x", "w_router", "w1", "w2", "dy"))
     bias = torch.from_numpy(inp["router_bias"]).cuda() if inp["router_bias"] is not None else None
-    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk)
+    ws = dm.Workspace(cfg.num_tokens, cfg.d_model, cfg.ffn_hidden, cfg.num_experts, cfg.top_k, cfg.normalize_topk,
+                      expert_capacity=cfg.expert_capacity, pad_to_capacity=cfg.pad_to_capacity)
 
     if accumulate:     # fp32 accumulators of a training loop with gradient accumulation (never zeroed here: timing only)
         acc = [torch.zeros(s_, dtype=torch.float32, device="cuda")
@@ -171,6 +172,8 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
     T, k, d, h, E = cfg.num_tokens, cfg.top_k, cfg.d_model, cfg.ffn_hidden, cfg.num_experts
     ms = elapsed * 1e3 / steps
     useful = cfg.useful_flops
+    if cfg.expert_capacity > 0:      # token dropping: only the kept assignments are useful work
+        useful = 12.0 * float(n_e.sum()) * d * h
     res = {
         "workload": cfg.name, "steps": steps, "ms_per_step": ms, "ms_per_step_median": median_ms,
         "useful_tflops": useful / (ms * 1e-3) / 1e12,
@@ -178,17 +181,18 @@ def run_config(cfg, steps, warmup, hipev, with_cpu, verbose=True, accumulate=Fal
         "pct_mfma_peak": 100.0 * useful / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "padded_tflops": 12.0 * P * d * h / (ms * 1e-3) / 1e12,
         "P": P, "nnz_blocks": nnz, "active_experts": active, "max_tokens_per_expert": int(n_e.max()),
+        "expert_capacity": cfg.expert_capacity, "kept_assignments": int(n_e.sum()),
         "stage_ms": {n: round(v, 5) for n, v in stage_ms.items()},
         "matmul_ms": round(sum(stage_ms[n] for n in MATMUL_STAGES), 5),
     }
-    if cfg.name in HBM_BOUND:
+    if cfg.name.split("@")[0] in HBM_BOUND:
         ab = algorithmic_bytes(dominant, T, k, d, h, E, P, active)
         ach = ab / (kernel_ms * 1e-3) / 1e9
         res["roofline"] = {"kernel": dominant, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant)),
                            "kernel_ms": kernel_ms, "algorithmic_bytes": ab}
     else:
-        fl = 2.0 * T * k * d * h
+        fl = useful / 6.0
         ach = fl / (kernel_ms * 1e-3) / 1e12
         res["roofline"] = {"kernel": dominant, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
@@ -242,8 +246,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--config", default="large_expert_top2",
                     help="headline workload: name (see dmoe_inputs.CONFIGS) or 1-based index; default = the largest")
-    ap.add_argument("--also", default="tiny,xs,small_zipf1.0,medium_zipf1.2_top2",
-                    help="comma-separated extra workloads reported under 'other_workloads' ('' for none)")
+    ap.add_argument("--also", default="tiny,xs,small_zipf1.0,medium_zipf1.2_top2,xs@cf1.0",
+                    help="comma-separated extra workloads reported under 'other_workloads' ('' for none); "
+                         "name@cfF = that workload as the token-dropping MoE of Section 2.2 with capacity factor F, "
+                         "every expert padded to its capacity")
     ap.add_argument("--also-steps", type=int, default=30, help="timed steps of each extra workload (>= 20)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-probe", action="store_true",
@@ -267,6 +273,12 @@ def main():
     torch.cuda.set_device(0)
 
     def pick(name):
+        if "@cf" in name:            # expert_capacity = num_tokens * top_k / num_experts * capacity_factor (Section 2.2)
+            import dataclasses
+            base_name, factor = name.split("@cf")
+            base = pick(base_name)
+            cap = max(1, int(base.num_tokens * base.top_k / base.num_experts * float(factor)))
+            return dataclasses.replace(base, name=name, expert_capacity=cap, pad_to_capacity=1)
         return CONFIGS[int(name) - 1] if name.isdigit() else CONFIG_BY_NAME[name]
 
     if args.copy_calibration:      # a kernel whose HBM traffic is known: reads 1 GiB, writes 1 GiB
