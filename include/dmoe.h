@@ -199,7 +199,7 @@ DMOE_API int dmoe_set_stage_events(void *events);
 DMOE_API int dmoe_set_tile_mode(int mode);
 
 /* ---- General block-sparse products (Sections 4.2, 5.1) ---------------------------------------------------------
- * The six products of the layer (and DDS, dense = dense x sparse, which the layer does not need) are general primitives on a 128x128 block-sparse matrix S of block_rows x block_cols
+ * The six products of the layer (and the other six that Section 5.1.1 counts, which the layer does not need) are general primitives on a 128x128 block-sparse matrix S of block_rows x block_cols
  * blocks with ANY mask; the dMoE topology is the block-diagonal instance.  These entry points expose them for a
  * caller-supplied mask, without the fused dMoE epilogues, one 128x128 block per workgroup.  Values of S: block b of
  * the row-wise order (ascending row, ascending column inside a row) is a contiguous row-major 128x128 bf16 tile at
@@ -214,9 +214,17 @@ DMOE_API int dmoe_set_tile_mode(int mode);
  *   DMOE_OP_DSDT  a = S         b = W [D,N]   out [M,D]  = S W^T
  *   DMOE_OP_DDTS  a = X [M,D]   b = S         out [D,N]  = X^T S      (through the transpose indices)
  *   DMOE_OP_DDS   a = X [D,M]   b = S         out [D,N]  = X S        (through the transpose indices; Section 5.1.1)
+ *
+ * The remaining combinations of transposed and non-transposed inputs (Section 5.1.1: every product with every
+ * combination), named like the paper's superscripts with the T after the operand's letter:
+ *   DMOE_OP_SDTD  a = X [D,M]   b = W [D,N]   out = S    S = (X^T W)   sampled on the mask
+ *   DMOE_OP_SDTDT a = X [D,M]   b = W [N,D]   out = S    S = (X^T W^T) sampled on the mask
+ *   DMOE_OP_DSTDT a = S         b = X [D,M]   out [N,D]  = S^T X^T     (through the transpose indices)
+ *   DMOE_OP_DDST  a = X [D,N]   b = S         out [D,M]  = X S^T       (block rows of S walked in the primary order)
+ *   DMOE_OP_DDTST a = X [N,D]   b = S         out [D,M]  = X^T S^T
  */
 enum { DMOE_OP_SDD = 0, DMOE_OP_DSD = 1, DMOE_OP_SDDT = 2, DMOE_OP_DSTD = 3, DMOE_OP_DSDT = 4, DMOE_OP_DDTS = 5,
-       DMOE_OP_DDS = 6 };
+       DMOE_OP_DDS = 6, DMOE_OP_SDTD = 7, DMOE_OP_SDTDT = 8, DMOE_OP_DSTDT = 9, DMOE_OP_DDST = 10, DMOE_OP_DDTST = 11 };
 
 /* Bytes of device memory that the topology of a mask with `nnz` nonzero blocks needs (host pointer out).
  * Errors: DMOE_EINVAL (dimensions < 1, 128*dimension >= 2^24, nnz out of range).                               */

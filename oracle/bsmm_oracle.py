@@ -12,6 +12,11 @@ present where `mask` is nonzero and absent (zero) elsewhere, the definitions are
     DS^TD Y = S^T X                                    DD^TS  Y = X^T S
     DDS   Y = X S     (dense output, sparse right input; named in Section 5.1.1, not used by the layer)
 
+and the remaining combinations of transposed inputs that Section 5.1.1 counts (a T after the operand's letter):
+
+    SD^TD   S = (X^T W)   on the mask                  SD^TD^T  S = (X^T W^T) on the mask
+    DS^TD^T Y = S^T X^T                                DDS^T    Y = X S^T            DD^TS^T  Y = X^T S^T
+
 and that is what this file writes out: densify, multiply in float64, restrict.  The values of S travel as
 [nnz, 128, 128] in the row-wise order of the nonzero blocks (ascending row, ascending column inside a row), which is
 the order of the blocked-CSR encoding (Section 5.1.3).
@@ -87,3 +92,29 @@ def ddts(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
 def dds(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
     """Y = X S.  x [D, M], Y [D, N]."""
     return x.astype(np.float64) @ densify(s.astype(np.float64), mask)
+
+
+# ---- the remaining combinations of transposed inputs (Section 5.1.1)
+def sdtd(x: np.ndarray, w: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """S = (X^T W) on the mask.  x [D, M], w [D, N]."""
+    return sample(x.astype(np.float64).T @ w.astype(np.float64), mask)
+
+
+def sdtdt(x: np.ndarray, w: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """S = (X^T W^T) on the mask.  x [D, M], w [N, D]."""
+    return sample(x.astype(np.float64).T @ w.astype(np.float64).T, mask)
+
+
+def dstdt(s: np.ndarray, x: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Y = S^T X^T.  x [D, M], Y [N, D]."""
+    return densify(s.astype(np.float64), mask).T @ x.astype(np.float64).T
+
+
+def ddst(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Y = X S^T.  x [D, N], Y [D, M]."""
+    return x.astype(np.float64) @ densify(s.astype(np.float64), mask).T
+
+
+def ddtst(x: np.ndarray, s: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Y = X^T S^T.  x [N, D], Y [D, M]."""
+    return x.astype(np.float64).T @ densify(s.astype(np.float64), mask).T

@@ -163,7 +163,7 @@ def dmoe_topology_counts_host(topo, stream=None):
     return list(out)
 
 
-OP_SDD, OP_DSD, OP_SDDT, OP_DSTD, OP_DSDT, OP_DDTS, OP_DDS = range(7)
+OP_SDD, OP_DSD, OP_SDDT, OP_DSTD, OP_DSDT, OP_DDTS, OP_DDS, OP_SDTD, OP_SDTDT, OP_DSTDT, OP_DDST, OP_DDTST = range(12)
 
 
 def dmoe_bsmm_sizes(block_rows: int, block_cols: int, nnz: int) -> int:
@@ -236,6 +236,32 @@ class BlockSparse:
             raise ValueError("x must have %d columns (got %d)" % (self.rows * 128, x.shape[1]))
         out = self._out(x.shape[0], self.cols * 128)
         dmoe_bsmm(OP_DDS, self.topo, self.rows, self.cols, self.nnz, x.shape[0], x, s, out, stream)
+        return out
+
+    # the remaining combinations of transposed inputs (a T after the operand's letter)
+    def sdtd(self, x, w, stream=None):       # x [D, M], w [D, N] -> S = X^T W on the mask
+        out = self._out(max(self.nnz, 1), 128, 128)
+        dmoe_bsmm(OP_SDTD, self.topo, self.rows, self.cols, self.nnz, x.shape[0], x, w, out, stream)
+        return out[:self.nnz]
+
+    def sdtdt(self, x, w, stream=None):      # x [D, M], w [N, D] -> S = X^T W^T on the mask
+        out = self._out(max(self.nnz, 1), 128, 128)
+        dmoe_bsmm(OP_SDTDT, self.topo, self.rows, self.cols, self.nnz, x.shape[0], x, w, out, stream)
+        return out[:self.nnz]
+
+    def dstdt(self, s, x, stream=None):      # x [D, M] -> S^T X^T [N, D]
+        out = self._out(self.cols * 128, x.shape[0])
+        dmoe_bsmm(OP_DSTDT, self.topo, self.rows, self.cols, self.nnz, x.shape[0], s, x, out, stream)
+        return out
+
+    def ddst(self, x, s, stream=None):       # x [D, N] -> X S^T [D, M]
+        out = self._out(x.shape[0], self.rows * 128)
+        dmoe_bsmm(OP_DDST, self.topo, self.rows, self.cols, self.nnz, x.shape[0], x, s, out, stream)
+        return out
+
+    def ddtst(self, x, s, stream=None):      # x [N, D] -> X^T S^T [D, M]
+        out = self._out(x.shape[1], self.rows * 128)
+        dmoe_bsmm(OP_DDTST, self.topo, self.rows, self.cols, self.nnz, x.shape[1], x, s, out, stream)
         return out
 
 

@@ -74,6 +74,11 @@ template <> struct OpLayouts<OP_DSTD> { static constexpr int A = NC, B = NC; };
 template <> struct OpLayouts<OP_DSDT> { static constexpr int A = KC, B = KC; };
 template <> struct OpLayouts<OP_DDTS> { static constexpr int A = NC, B = NC; };
 template <> struct OpLayouts<OP_DDS>  { static constexpr int A = KC, B = NC; };
+template <> struct OpLayouts<OP_SDTD>  { static constexpr int A = NC, B = NC; };   // S = X^T W    (X given as [D, M])
+template <> struct OpLayouts<OP_SDTDT> { static constexpr int A = NC, B = KC; };   // S = X^T W^T
+template <> struct OpLayouts<OP_DSTDT> { static constexpr int A = NC, B = KC; };   // Y = S^T X^T  (X given as [D, M])
+template <> struct OpLayouts<OP_DDST>  { static constexpr int A = KC, B = KC; };   // Y = X S^T    (S walked by rows)
+template <> struct OpLayouts<OP_DDTST> { static constexpr int A = NC, B = KC; };   // Y = X^T S^T  (X given as [N, D])
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup w runs on XCD w % 8).  Work items are cut into
 // patches of P consecutive items that share operands; patch p goes to XCD p % 8, so the items of a patch run
@@ -128,8 +133,10 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   constexpr int WB = NW / (PA * PB);                // waves per 128x128 block of the tile
   constexpr int MI = 8 / WB;
   static_assert(WB == 2 || WB == 4 || WB == 8, "unsupported tile / workgroup shape");
-  constexpr bool kSparseOut = OP == OP_SDD || OP == OP_SDDT;
-  constexpr bool kRowMajor = kSparseOut || OP == OP_DSD || OP == OP_DSDT;   // items enumerate block rows
+  constexpr bool kSparseOut = OP == OP_SDD || OP == OP_SDDT || OP == OP_SDTD || OP == OP_SDTDT;
+  constexpr bool kRowsInB = OP == OP_DDST || OP == OP_DDTST;   // dense x sparse^T: the block rows of S are the B panel
+  constexpr bool kRowMajor = kSparseOut || OP == OP_DSD || OP == OP_DSDT || kRowsInB;   // items enumerate block rows
+  static_assert(OP < OP_SDTD || PA * PB == 1, "the products beyond the layer's run one 128x128 block per workgroup");
   // The 256x256 tiles of the token-row products run as a persistent, software-pipelined loop over the items of a
   // workgroup (see the end of the kernel); everything else takes one item at a time.
   constexpr bool kPipe = kRowMajor && PA == 2 && PB == 2 && NS == 2 && NW == 8;
@@ -227,7 +234,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       // The rows of an expert beyond its token count are padding (Section 5.2): zero in both operands of a weight
       // gradient, so K tiles that lie entirely in the padding of the last block are skipped.
       if (p.tokens_per_expert) t.nk = min(t.nk, (p.tokens_per_expert[e] + BK - 1) / BK);
-      if constexpr (OP == OP_DSTD) { t.a_ok1 = second_col;  t.b_ok1 = second_d; }
+      if constexpr (OP == OP_DSTD || OP == OP_DSTDT) { t.a_ok1 = second_col;  t.b_ok1 = second_d; }
       else                         { t.a_ok1 = second_d;    t.b_ok1 = second_col; }
       return true;
     }
@@ -242,6 +249,11 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   else if constexpr (OP == OP_DSDT) { lda = kBlock; ldb = (uint32_t)ldw; }
   else if constexpr (OP == OP_DSTD) { lda = kBlock; ldb = d; }
   else if constexpr (OP == OP_DDS)  { lda = (uint32_t)p.ka;  ldb = kBlock; }
+  else if constexpr (OP == OP_SDTD)  { lda = (uint32_t)p.ka;  ldb = (uint32_t)ldw; }
+  else if constexpr (OP == OP_SDTDT) { lda = (uint32_t)p.ka;  ldb = d; }
+  else if constexpr (OP == OP_DSTDT) { lda = kBlock;  ldb = (uint32_t)p.ka; }
+  else if constexpr (OP == OP_DDST)  { lda = (uint32_t)ldw;  ldb = kBlock; }
+  else if constexpr (OP == OP_DDTST) { lda = d;  ldb = kBlock; }
   else                              { lda = d;      ldb = kBlock; }
 
   // The K loop of the products that walk the topology needs one to three index values per sparse block.  They are
@@ -251,9 +263,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   auto refill = [&](TileState& t, int kb0) {
     const int n = (t.nk + kSub - 1) / kSub - kb0;   // blocks left from kb0 on (the last one may be cut short)
     if (lane < n) {
-      if constexpr (OP == OP_DSD || OP == OP_DSDT) {
+      if constexpr (OP == OP_DSD || OP == OP_DSDT || kRowsInB) {
         t.ix0 = p.column_indices[t.first0 + kb0 + lane];
-      } else if constexpr (OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS) {
+      } else if constexpr (OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS || OP == OP_DSTDT) {
         t.ix0 = p.block_offsets_t[t.first0 + kb0 + lane];
         t.ix1 = p.block_offsets_t[t.first1 + kb0 + lane];
         t.ix2 = p.row_indices_t[t.first0 + kb0 + lane];
@@ -274,6 +286,38 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       a1 = p.dense_a + (size_t)t.r1 * kBlock * d + kt * BK;
       b0 = p.dense_b + (size_t)t.c0 * kBlock * d + kt * BK;
       b1 = p.dense_b + (size_t)t.c1 * kBlock * d + kt * BK;
+    } else if constexpr (OP == OP_SDTD || OP == OP_SDTDT) {
+      // the left input is given transposed, [D, M]: its K index is the strided one
+      a0 = p.dense_a + (size_t)kt * BK * lda + (size_t)t.r0 * kBlock;
+      a1 = p.dense_a + (size_t)kt * BK * lda + (size_t)t.r1 * kBlock;
+      if constexpr (OP == OP_SDTD) {
+        b0 = p.dense_b + (size_t)kt * BK * ldw + (size_t)t.c0 * kBlock;
+        b1 = p.dense_b + (size_t)kt * BK * ldw + (size_t)t.c1 * kBlock;
+      } else {
+        b0 = p.dense_b + (size_t)t.c0 * kBlock * d + kt * BK;
+        b1 = p.dense_b + (size_t)t.c1 * kBlock * d + kt * BK;
+      }
+    } else if constexpr (kRowsInB) {
+      // Y = X S^T (or X^T S^T): output block-column r is block-row r of S; its blocks (r, col), walked in the primary
+      // order, are the B operand as they lie in memory ([n][k], k contiguous); X supplies the block-column col
+      const int kb = kt / kSub, half = kt % kSub;
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
+      if constexpr (OP == OP_DDST) a0 = p.dense_a + (size_t)t.jd0 * kBlock * lda + (size_t)col * kBlock + half * BK;
+      else                         a0 = p.dense_a + ((size_t)col * kBlock + half * BK) * lda + (size_t)t.jd0 * kBlock;
+      a1 = a0;
+      b0 = p.sparse_in + (size_t)(t.first0 + kb) * kBlockElems + half * BK;
+      b1 = b0;
+    } else if constexpr (OP == OP_DSTDT) {
+      // Y = S^T X^T with X given as [D, M]: as DS^TD, but the dense operand has its K index contiguous
+      const int i = kt / kSub, half = kt % kSub;
+      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
+      const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
+      a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
+      a1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
+      b0 = p.dense_a + (size_t)t.jd0 * kBlock * ldb + (size_t)row * kBlock + half * BK;
+      b1 = b0;
     } else if constexpr (OP == OP_DSD) {
       const int kb = kt / kSub, half = kt % kSub;
       if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
@@ -409,7 +453,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       out = p.out0 + blk;  ldo = kBlock;
     } else if constexpr (OP == OP_DSD || OP == OP_DSDT) {
       out = p.out0 + ((size_t)(pm ? t.r1 : t.r0) * kBlock + arow0) * d + (size_t)(t.jd0 + pn) * kBlock + hn * 64;  ldo = d;
-    } else if constexpr (OP == OP_DSTD) {
+    } else if constexpr (kRowsInB) {
+      out = p.out0 + ((size_t)t.jd0 * kBlock + arow0) * p.ka + (size_t)t.r0 * kBlock + hn * 64;  ldo = p.ka;
+    } else if constexpr (OP == OP_DSTD || OP == OP_DSTDT) {
       out = p.out0 + ((size_t)(pm ? t.c1 : t.c0) * kBlock + arow0) * d + (size_t)(t.jd0 + pn) * kBlock + hn * 64;  ldo = d;
     } else {
       out = p.out0 + ((size_t)(t.jd0 + pm) * kBlock + arow0) * ldw + (size_t)(pn ? t.c1 : t.c0) * kBlock + hn * 64;  ldo = ldw;
@@ -783,7 +829,7 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
   int grid = ((items + 8 * kPatch - 1) / (8 * kPatch)) * (8 * kPatch);   // whole patches on every XCD
   BsParams q = p;
   q.items = grid;
-  constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS;
+  constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS || OP == OP_DSTDT;
   if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
   // the 256x256 tiles of the token-row products run as a persistent loop: one workgroup per CU (128 KB of LDS each)
   constexpr bool pipe = !grad && PA == 2 && PB == 2 && NS == 2 && NW == 8;
@@ -811,6 +857,13 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
   const int hb = p.hb, db = p.db;
   constexpr bool row_major = OP == OP_SDD || OP == OP_SDDT || OP == OP_DSD || OP == OP_DSDT;
   constexpr bool sparse_out = OP == OP_SDD || OP == OP_SDDT;
+  if constexpr (OP >= OP_SDTD) {
+    // general masks only, one block per workgroup: sparse outputs enumerate the nonzero blocks, Y = X S^T the block
+    // rows of S times the row blocks of X, Y = S^T X^T the block columns times the row blocks of X
+    if constexpr (OP == OP_SDTD || OP == OP_SDTDT) launch_variant<OP, 1, 1, 2, 8>(p, a.nnz, 1, s);
+    else if constexpr (OP == OP_DSTDT)             launch_variant<OP, 1, 1, 2, 8>(p, a.E * hb, db, s);
+    else                                           launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, db, s);
+  } else {
   const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
   if (row_major) {
     bool small = (long long)a.groups_est * big_minor < 256 + (sparse_out ? 1 : 0);
@@ -845,6 +898,7 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
     launch_variant<OP, 2, 2, 2, 8>(p, a.E * ((hb + 1) / 2), big_minor, s);
     launch_variant<OP, 1, 1, 2, 8>(p, a.E * hb, db, s);
   }
+  }
 }
 
 void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
@@ -867,7 +921,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the
   // workgroup -> XCD assignment is static, so they are dealt out one by one to keep the eight XCDs level, unless
   // the routing is even enough for patches (sched[1], decided on the device).
-  p.patch = (op == OP_DSTD || op == OP_DDTS || op == OP_DDS) ? 1 : -kPatchSlack;
+  p.patch = (op == OP_DSTD || op == OP_DDTS || op == OP_DDS || op == OP_DSTDT) ? 1 : -kPatchSlack;
   switch (op) {
     case OP_SDD:  launch_one<OP_SDD>(p, a, s); break;
     case OP_SDDT: launch_one<OP_SDDT>(p, a, s); break;
@@ -876,6 +930,11 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
     case OP_DSTD: launch_one<OP_DSTD>(p, a, s); break;
     case OP_DDTS: launch_one<OP_DDTS>(p, a, s); break;
     case OP_DDS:  launch_one<OP_DDS>(p, a, s); break;
+    case OP_SDTD:  launch_one<OP_SDTD>(p, a, s); break;
+    case OP_SDTDT: launch_one<OP_SDTDT>(p, a, s); break;
+    case OP_DSTDT: launch_one<OP_DSTDT>(p, a, s); break;
+    case OP_DDST:  launch_one<OP_DDST>(p, a, s); break;
+    case OP_DDTST: launch_one<OP_DDTST>(p, a, s); break;
   }
 }
 

@@ -169,7 +169,7 @@ int dmoe_bsmm_topology(const uint8_t* mask, int block_rows, int block_cols, void
 
 int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_cols, int nnz, int dense, const void* a,
               const void* b, void* out, void* stream) {
-  if (op < DMOE_OP_SDD || op > DMOE_OP_DDS) return fail(DMOE_EINVAL, "unknown product %d", op);
+  if (op < DMOE_OP_SDD || op > DMOE_OP_DDTST) return fail(DMOE_EINVAL, "unknown product %d", op);
   if (!topo || !topo->row_offsets || !topo->counts) return fail(DMOE_EINVAL, "topology is NULL or not built");
   if (int rc = check_mask_dims(block_rows, block_cols, nnz)) return rc;
   if (dense < kBlock || dense % kBlock) return fail(DMOE_EINVAL, "dense must be a positive multiple of 128 (got %d)", dense);
@@ -177,7 +177,8 @@ int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_col
   if ((long long)block_cols * kBlock * dense >= (1ll << 40) || (long long)block_cols * kBlock * kBlock >= (1ll << 32) ||
       (long long)block_rows * kBlock * kBlock >= (1ll << 32))
     return fail(DMOE_EINVAL, "operands too large");
-  if ((op == DMOE_OP_SDD || op == DMOE_OP_SDDT) && nnz == 0) return DMOE_OK;      // no block to write
+  const bool sparse_out = op == DMOE_OP_SDD || op == DMOE_OP_SDDT || op == DMOE_OP_SDTD || op == DMOE_OP_SDTDT;
+  if (sparse_out && nnz == 0) return DMOE_OK;      // no block to write
   if (int rc = check_ptr(a, "a")) return rc;
   if (int rc = check_ptr(b, "b")) return rc;
   if (int rc = check_ptr(out, "out")) return rc;
@@ -195,6 +196,11 @@ int dmoe_bsmm(int op, const dmoe_topology_t* topo, int block_rows, int block_col
     case DMOE_OP_DSDT: g.sparse_in = pa;  g.dense_b = pb;  break;    // Y = S W^T
     case DMOE_OP_DDTS: g.dense_a = pa;  g.sparse_in = pb;  break;    // Y = X^T S
     case DMOE_OP_DDS:  g.dense_a = pa;  g.sparse_in = pb;  g.ka = block_rows * kBlock;  break;   // Y = X S
+    case DMOE_OP_SDTD:  g.dense_a = pa;  g.dense_b = pb;  g.ka = block_rows * kBlock;  break;    // S = X^T W
+    case DMOE_OP_SDTDT: g.dense_a = pa;  g.dense_b = pb;  g.ka = block_rows * kBlock;  break;    // S = X^T W^T
+    case DMOE_OP_DSTDT: g.sparse_in = pa;  g.dense_a = pb;  g.ka = block_rows * kBlock;  break;  // Y = S^T X^T
+    case DMOE_OP_DDST:  g.dense_a = pa;  g.sparse_in = pb;  g.ka = block_rows * kBlock;  break;  // Y = X S^T
+    case DMOE_OP_DDTST: g.dense_a = pa;  g.sparse_in = pb;  g.ka = block_rows * kBlock;  break;  // Y = X^T S^T
   }
   (void)hipGetLastError();
   launch_bsmm(static_cast<BsOp>(op), g, static_cast<hipStream_t>(stream));

@@ -82,7 +82,11 @@ void launch_router_bwd(const dmoe_config& c, const dmoe_topology_t& t, const bf1
                        bf16_t* dx, float* dw_router, bool accumulate, hipStream_t s);
 int router_bwd_num_partials(const dmoe_config& c);
 
-enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5, OP_DDS = 6 };
+// The products the layer uses (0-5), DDS, and the remaining combinations of transposed inputs (Section 5.1.1), which
+// exist for general masks only (one 128x128 block per workgroup): a superscript T in the paper's notation is a `T`
+// after the operand's letter here (SDTD = S D^T D: the left dense input is given transposed).
+enum BsOp { OP_SDD = 0, OP_DSD = 1, OP_SDDT = 2, OP_DSTD = 3, OP_DSDT = 4, OP_DDTS = 5, OP_DDS = 6,
+            OP_SDTD = 7, OP_SDTDT = 8, OP_DSTDT = 9, OP_DDST = 10, OP_DDTST = 11 };
 struct BsArgs {
   const dmoe_topology_t* topo;
   int d, h, E;
@@ -91,7 +95,7 @@ struct BsArgs {
   int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
   int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
   int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
-  int ka;                  // DDS only: leading dimension of dense_a (= 128 * block rows of S)
+  int ka;                  // DDS and the products of Section 5.1.1 beyond the layer's: 128 * block rows of S
   int act;                 // SDD's fused activation: 0 exact (erf) GELU, 1 tanh form
   int coo;                 // 1 (general masks): SDD / SDD^T enumerate the nonzero blocks through row_indices
   int nnz;                 // ... and this many of them

@@ -54,7 +54,7 @@ MASKS = {
 
 @pytest.mark.parametrize("name", list(MASKS))
 @pytest.mark.parametrize("dense", [128, 384])
-def test_six_products_on_a_mask(name, dense):
+def test_all_products_on_a_mask(name, dense):
     import paper_2211_15841_amd as dm
     rng = np.random.default_rng(zlib.crc32(("%s/%d" % (name, dense)).encode()))
     mask = MASKS[name](rng)
@@ -79,6 +79,19 @@ def test_six_products_on_a_mask(name, dense):
     _close(_host(bs.ddts(xd, sd)), bo.ddts(x, s, mask), "DD^TS")
     xtb, xt = _bf16(rng, (D, M))
     _close(_host(bs.dds(_dev(xtb), sd)), bo.dds(xt, s, mask), "DDS")
+
+    # the remaining combinations of transposed inputs (Section 5.1.1)
+    xdm_b, xdm = xtb, xt                                   # [D, M]
+    xdn_b, xdn = _bf16(rng, (D, N))
+    xnd_b, xnd = _bf16(rng, (N, D))
+    _close(_host(bs.sdtd(_dev(xdm_b), wdn_d)), bo.sdtd(xdm, wdn, mask), "SD^TD")
+    _close(_host(bs.sdtdt(_dev(xdm_b), wnd_d)), bo.sdtdt(xdm, wnd, mask), "SD^TD^T")
+    _close(_host(bs.dstdt(sd, _dev(xdm_b))), bo.dstdt(s, xdm, mask), "DS^TD^T")
+    u = _host(bs.ddst(_dev(xdn_b), sd))
+    _close(u, bo.ddst(xdn, s, mask), "DDS^T")
+    _close(_host(bs.ddtst(_dev(xnd_b), sd)), bo.ddtst(xnd, s, mask), "DD^TS^T")
+    for r in np.nonzero(~mask.any(axis=1))[0]:            # a block row of S without blocks: zero columns of X S^T
+        assert not u[:, r * 128:(r + 1) * 128].any()
 
     # rows / columns without blocks must come out as exact zeros
     y = _host(bs.dsd(sd, wnd_d))

@@ -111,3 +111,43 @@ def test_dds_is_the_transpose_of_a_sparse_times_dense_product_and_the_adjoint_of
     g = rng.standard_normal((D, C * 128))
     np.testing.assert_allclose(float((y * g).sum()), float((s * bo.sdd(x.T.copy(), g, mask)).sum()), rtol=1e-10)
     assert y.shape == (D, C * 128)
+
+
+def test_remaining_transposition_combinations_against_scipy_and_the_pinned_products():
+    """The five products beyond the layer's seven (Section 5.1.1: every combination of transposed inputs), each pinned
+    three ways: a scipy block-CSR product at the full block size, the already pinned product of the explicitly
+    transposed input, and an adjoint identity."""
+    rng = np.random.default_rng(61)
+    mask = np.array([[1, 0, 1], [0, 0, 1], [1, 1, 0], [0, 0, 0]], dtype=np.uint8)
+    R, C, D = mask.shape[0], mask.shape[1], 256
+    M, N = R * 128, C * 128
+    s = rng.standard_normal((int(mask.sum()), 128, 128))
+    indptr = np.concatenate([[0], np.cumsum(mask.astype(bool).sum(axis=1))])
+    S = sp.bsr_matrix((s, np.nonzero(mask)[1], indptr), shape=(M, N), blocksize=(128, 128))
+    x_dm, x_dn, x_nd = rng.standard_normal((D, M)), rng.standard_normal((D, N)), rng.standard_normal((N, D))
+    w_dn, w_nd = rng.standard_normal((D, N)), rng.standard_normal((N, D))
+
+    # sparse outputs: the masked blocks of the dense product
+    full = x_dm.T @ w_dn
+    keep = np.kron(mask, np.ones((128, 128)))
+    np.testing.assert_allclose(bo.densify(bo.sdtd(x_dm, w_dn, mask), mask), full * keep, rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(bo.sdtd(x_dm, w_dn, mask), bo.sdd(x_dm.T.copy(), w_dn, mask))
+    np.testing.assert_allclose(bo.densify(bo.sdtdt(x_dm, w_nd, mask), mask), (x_dm.T @ w_nd.T) * keep, rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(bo.sdtdt(x_dm, w_nd, mask), bo.sddt(x_dm.T.copy(), w_nd, mask))
+
+    # dense outputs: scipy's own sparse products
+    np.testing.assert_allclose(bo.dstdt(s, x_dm, mask), S.T.tocsr() @ x_dm.T, rtol=1e-12, atol=1e-10)
+    np.testing.assert_array_equal(bo.dstdt(s, x_dm, mask), bo.dstd(s, x_dm.T.copy(), mask))
+    np.testing.assert_allclose(bo.ddst(x_dn, s, mask), (S @ x_dn.T).T, rtol=1e-12, atol=1e-10)
+    np.testing.assert_allclose(bo.ddst(x_dn, s, mask), bo.dsd(s, x_dn.T.copy(), mask).T, rtol=1e-12, atol=1e-10)
+    np.testing.assert_allclose(bo.ddtst(x_nd, s, mask), (S @ x_nd).T, rtol=1e-12, atol=1e-10)
+    np.testing.assert_allclose(bo.ddtst(x_nd, s, mask), bo.dsd(s, x_nd, mask).T, rtol=1e-12, atol=1e-10)
+    assert bo.ddst(x_dn, s, mask).shape == (D, M) and bo.dstdt(s, x_dm, mask).shape == (N, D)
+    # a row of S without blocks is a zero COLUMN of X S^T
+    assert not bo.ddst(x_dn, s, mask)[:, 3 * 128:].any()
+
+    # adjoints: <X S^T, G> = <S, G^T X on the mask>,  <S^T X^T, G> = <S, X^T G^T on the mask>
+    g = rng.standard_normal((D, M))
+    np.testing.assert_allclose(float((bo.ddst(x_dn, s, mask) * g).sum()), float((s * bo.sdtd(g, x_dn, mask)).sum()), rtol=1e-10)
+    g2 = rng.standard_normal((N, D))
+    np.testing.assert_allclose(float((bo.dstdt(s, x_dm, mask) * g2).sum()), float((s * bo.sdtdt(x_dm, g2, mask)).sum()), rtol=1e-10)
