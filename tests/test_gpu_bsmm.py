@@ -126,3 +126,37 @@ def test_topology_of_a_mask_is_bit_exact():
     np.testing.assert_array_equal(arr("column_offsets_t", mask.shape[1] + 1), enc["column_offsets_t"])
     np.testing.assert_array_equal(arr("row_indices_t", nnz), enc["row_indices_t"])
     np.testing.assert_array_equal(arr("block_offsets_t", nnz), enc["block_offsets_t"])
+
+
+def test_variable_width_experts_through_the_general_products():
+    """Figure 3C draws a block-diagonal matrix whose blocks differ in rows AND columns; Section 4.1 notes that the column
+    count could vary per expert (experts of different hidden sizes) and leaves it unexplored.  The general products
+    take any mask, so such a layer is a mask away: three experts with 1, 3 and 2 block-columns and 2, 1 and 3
+    block-rows of tokens, SDD for the first layer and DSD for the second, against one dense product pair per expert."""
+    import paper_2211_15841_amd as dm
+    rng = np.random.default_rng(91)
+    rows, widths, D = [2, 1, 3], [1, 3, 2], 256
+    R, C = sum(rows), sum(widths)
+    mask = np.zeros((R, C), dtype=np.uint8)
+    r0 = c0 = 0
+    spans = []
+    for nr, nc in zip(rows, widths):
+        mask[r0:r0 + nr, c0:c0 + nc] = 1
+        spans.append((r0 * 128, (r0 + nr) * 128, c0 * 128, (c0 + nc) * 128))
+        r0, c0 = r0 + nr, c0 + nc
+    xb, x = _bf16(rng, (R * 128, D))
+    w1b, w1 = _bf16(rng, (D, C * 128), 0.05)
+    w2b, w2 = _bf16(rng, (C * 128, D), 0.05)
+    bs = dm.BlockSparse(mask)
+    h_blocks = bs.sdd(_dev(xb), _dev(w1b))
+    y = _host(bs.dsd(h_blocks, _dev(w2b)))
+    h_ref = np.zeros((R * 128, C * 128))
+    y_ref = np.zeros((R * 128, D))
+    hb = _host(h_blocks)
+    for (ra, rb, ca, cb) in spans:                        # per expert: two dense products on its own tokens and width
+        h_e = x[ra:rb] @ w1[:, ca:cb]
+        h_ref[ra:rb, ca:cb] = h_e
+        # the second layer consumes what the first one stored (bf16), as the GPU path does
+        y_ref[ra:rb] = bo.densify(hb, mask)[ra:rb, ca:cb] @ w2[ca:cb]
+    _close(hb, bo.sample(h_ref, mask), "variable-width SDD")
+    _close(y, y_ref, "variable-width DSD")
