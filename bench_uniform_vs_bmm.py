@@ -1,7 +1,9 @@
 #!/usr/bin/env python3
 """Kernel-level comparison in the style of the paper's Figure 9 (Section 6.3): the six block-sparse products of
-the dMoE layer under a UNIFORM assignment of tokens to experts.  (The paper sets them against the vendor's dense
-batched matrix multiplication on the same shapes; that half is not run here, see --vendor-gemm.)
+the dMoE layer under a UNIFORM assignment of tokens to experts, set against the vendor library's dense batched
+matrix multiplication on the same shapes (rocBLAS strided-batched bf16 GEMM, timed by the stand-alone program
+bench_vendor_bmm.cpp, which this script runs as a child process BEFORE it touches the GPU itself: the two sides
+never share a process).
 
 Section 6.3 benchmarks the forward, backward-data and backward-weight products of both FFN layers for the
 per-GPU problems of dMoE-XS, -Small and -Medium (64 experts over 8 GPUs = 8 local experts; micro-batch sizes of
@@ -12,10 +14,13 @@ problems in all, metadata construction excluded.  This script does the same on o
     every expert owns T/E rows and no padding is added (T/E is a multiple of 128);
   * each block-sparse product is timed with HIP events recorded around that kernel inside dmoe_forward /
     dmoe_backward (SDD includes its fused GELU epilogue and writes two tensors, SDD^T its fused multiplication);
+  * the vendor side multiplies one contiguous matrix pair per expert, the layout that suits it best, and does no
+    epilogue work.
 
-Prints one JSON line.
+Prints one JSON line with, per problem, both throughputs and their ratio (the paper reports 98.6 % of cuBLAS on
+average on its A100s).
 
-    python bench_uniform_vs_bmm.py [--iters 20] [--models xs,small,medium]
+    python bench_uniform_vs_bmm.py [--iters 20] [--models xs,small,medium] [--no-vendor]
 """
 from __future__ import annotations
 
@@ -45,16 +50,33 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--models", default="xs,small,medium")
+    ap.add_argument("--no-vendor", action="store_true", help="skip the rocBLAS child process (block-sparse side only)")
     ap.add_argument("--vendor-gemm", action="store_true",
-                    help="REFUSED.  Timing torch.bmm on the same shapes once ended in a GPU memory fault reported by "
-                         "the synchronize after the torch.bmm loop; its cause was never established, so that "
-                         "comparison is not run and the flag exits with an error before any GPU work")
+                    help="REFUSED.  Timing torch.bmm inside this process, after the library's steps, once ended in a GPU "
+                         "memory fault reported by the synchronize after the torch.bmm loop; its cause was never "
+                         "established, so that in-process form is not run (the vendor side now runs in its own process)")
     args = ap.parse_args()
     if args.vendor_gemm:
-        print("bench_uniform_vs_bmm.py: --vendor-gemm is refused (an earlier run of the vendor batched GEMM in this "
-              "process ended in a GPU memory fault of unknown cause); only the block-sparse side is measured",
+        print("bench_uniform_vs_bmm.py: --vendor-gemm is refused (an earlier run of torch.bmm in this process ended in a "
+              "GPU memory fault of unknown cause); the vendor side runs as a separate rocBLAS program by default",
               file=sys.stderr)
         sys.exit(2)
+
+    # the vendor's side first, in a process of its own, before this one initialises the GPU
+    vendor = {}
+    if not args.no_vendor:
+        import subprocess
+        from paper_2211_15841_amd.build import VENDOR_BENCH
+        if not os.path.exists(VENDOR_BENCH):
+            print("bench_uniform_vs_bmm.py: %s is not built (run __graft_entry__.build())" % VENDOR_BENCH, file=sys.stderr)
+            sys.exit(2)
+        r = subprocess.run([VENDOR_BENCH, "--iters", str(max(args.iters, 20))], capture_output=True, text=True, timeout=300)
+        sys.stderr.write(r.stderr)
+        if r.returncode != 0:
+            print("bench_uniform_vs_bmm.py: the vendor GEMM program failed (rc %d)" % r.returncode, file=sys.stderr)
+            sys.exit(3)
+        for q in json.loads(r.stdout.strip().splitlines()[-1])["problems"]:
+            vendor[(q["model"], q["product"])] = q
 
     import torch
     import paper_2211_15841_amd as dm
@@ -108,18 +130,29 @@ def main():
 
         flops = 2.0 * T * d * h
         for p in PRODUCTS:
-            rows.append({"model": name, "product": p, "what": LABEL[p], "tokens": T, "hidden": d, "ffn": h,
-                         "experts": E, "block_sparse_ms": round(ours[p], 4),
-                         "block_sparse_tflops": round(flops / ours[p] / 1e9, 1)})
-            print("[fig9] %-6s %-28s block-sparse %.3f ms (%.0f TFLOP/s)"
-                  % (name, LABEL[p], ours[p], flops / ours[p] / 1e9), file=sys.stderr, flush=True)
+            row = {"model": name, "product": p, "what": LABEL[p], "tokens": T, "hidden": d, "ffn": h,
+                   "experts": E, "block_sparse_ms": round(ours[p], 4),
+                   "block_sparse_tflops": round(flops / ours[p] / 1e9, 1)}
+            v = vendor.get((name, p))
+            if v:
+                row.update(vendor_ms=v["ms"], vendor_tflops=v["tflops"], relative=round(v["ms"] / ours[p], 3))
+                ratios.append(v["ms"] / ours[p])
+            rows.append(row)
+            print("[fig9] %-6s %-28s block-sparse %.3f ms (%.0f TFLOP/s)%s"
+                  % (name, LABEL[p], ours[p], flops / ours[p] / 1e9,
+                     ", rocBLAS batched %.3f ms (%.0f TFLOP/s): %.0f %% of it" % (v["ms"], v["tflops"], 100 * v["ms"] / ours[p])
+                     if v else ""), file=sys.stderr, flush=True)
         del x, w1, w2, dy
         torch.cuda.empty_cache()
     tf = [r["block_sparse_tflops"] for r in rows]
     print(json.dumps({"metric": "block-sparse product throughput under uniform routing (Figure 9 problems)",
                       "unit": "TFLOP/s", "mean": round(sum(tf) / len(tf), 1), "min": min(tf), "max": max(tf),
                       "n_problems": len(tf), "dtype": "bf16",
-                      "vendor_gemm": "not run: the dense batched GEMM of the vendor library is not timed by this script",
+                      "vendor_gemm": ("rocBLAS strided-batched bf16 GEMM (fp32 accumulation), one contiguous matrix pair per "
+                                      "expert, timed by bench_vendor_bmm in a process of its own") if ratios else "not run",
+                      "relative_throughput_mean": round(sum(ratios) / len(ratios), 3) if ratios else None,
+                      "relative_throughput_min": round(min(ratios), 3) if ratios else None,
+                      "relative_throughput_max": round(max(ratios), 3) if ratios else None,
                       "problems": rows}))
 
 if __name__ == "__main__":

@@ -54,5 +54,18 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+VENDOR_BENCH = os.path.join(BUILD, "bench_vendor_bmm")
+
+
+def build_vendor_bench() -> str:
+    """Compile the stand-alone rocBLAS batched-GEMM timing program (the vendor side of the Figure-9 comparison)."""
+    os.makedirs(BUILD, exist_ok=True)
+    src = os.path.join(HERE, "..", "bench_vendor_bmm.cpp")
+    _run([HIPCC, "--offload-arch=gfx950", "-O2", "-Wno-unused-result", src, "-L/opt/rocm/lib", "-lrocblas",
+          "-Wl,-rpath,/opt/rocm/lib", "-o", VENDOR_BENCH])
+    return VENDOR_BENCH
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
+    print(build_vendor_bench())
