@@ -54,6 +54,7 @@ struct BsParams {
   const int32_t* counts;
   const int32_t* sched;
   const int32_t* tokens_per_expert;   // dMoE topologies only (NULL for a general mask): lets the weight gradients skip padding
+  const int32_t* token_of;            // dMoE topologies only: tells a block row whose second half is all padding (a fringe)
   int d, h, E, hb, db;
   int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
@@ -117,6 +118,7 @@ struct TileState {
   int nk;                          // K tiles
   int r0, r1, first0, first1, c0, c1, jd0;
   int ix0, ix1, ix2;               // lane-distributed topology indices of the K loop (see refill)
+  int live;                        // 128, or 64 when rows 64..127 of the tile's block row are padding (one-block-row tiles)
 };
 
 template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
@@ -140,6 +142,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // The 256x256 tiles of the token-row products run as a persistent, software-pipelined loop over the items of a
   // workgroup (see the end of the kernel); everything else takes one item at a time.
   constexpr bool kPipe = kRowMajor && PA == 2 && PB == 2 && NS == 2 && NW == 8;
+  // tiles of one block row of the token-row products of the layer skip the padding half of a fringe block row
+  constexpr bool kFringe = kRowMajor && PA == 1 && NS == 2 && NW == 8 && BK == 64 && OP <= OP_DDTS;
   constexpr int kEpRows = MI >= 2 ? 64 : 32;        // rows of the wave's tile that pass through its staging tile at a time
   constexpr int kEpBytes = kEpRows * 128;           // per wave: 8 KB (4 KB for the 32-row waves)
   extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A slabs, B slabs]
@@ -179,6 +183,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     t.a_ok1 = false;  t.b_ok1 = false;
     t.nk = 0;  t.r0 = t.r1 = t.first0 = t.first1 = t.c0 = t.c1 = t.jd0 = 0;
     t.ix0 = t.ix1 = t.ix2 = 0;
+    t.live = kBlock;
     if constexpr (kRowMajor) {
       if (major >= majors_live) return false;
       if (coo_launch) {
@@ -196,6 +201,13 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
         t.a_ok1 = rg & 1;
       } else {
         t.r0 = major;
+        // Partial fringe blocks (Section 5.2 pads every expert to whole blocks; Section 6.2 notes the cost at small
+        // batches): when the last block row of an expert holds at most 64 tokens, rows 64..127 are padding.  Nothing
+        // downstream reads them -- the gathers go through row_of, and the weight gradients skip K tiles of 64 rows
+        // that lie wholly in padding -- so a tile of one block row neither loads, multiplies nor writes that half.
+        if constexpr (kFringe) {
+          if (p.token_of && p.token_of[(size_t)major * kBlock + 64] < 0) t.live = 64;
+        }
       }
       t.r1 = t.a_ok1 ? t.r0 + 1 : t.r0;
       t.first0 = p.row_offsets[t.r0];
@@ -392,11 +404,13 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
                  : : "v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
   };
   // part 0 = the A slabs, part 1 = the B slabs (issued at different points of the MFMA loop, see below)
+  int live_rows = kBlock;            // rows of the (single) A panel that are loaded: 64 for a fringe block row
   auto issue_loads = [&](int stage, int part) {
     const uint32_t s = __builtin_amdgcn_readfirstlane(lds_base + stage * kStageBytes + wave * 1024);
 #pragma unroll
     for (int i = 0; i < kCpw; ++i) {
       if (part == 0) {
+        if (kFringe && i * NW * 8 >= 64 && live_rows <= 64) continue;      // chunk i holds rows 8 (wave + NW i) ...
         dma16(a0, oa[i], s + NW * 1024 * i);
         if (PA == 2) dma16(a1, oa[i], s + kPanelBytes + NW * 1024 * i);
       } else {
@@ -721,7 +735,10 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   clear_acc();
   stamp(wgi, 0, nk);
   stamp(wgi, 1, nk);
-  const bool mine = (pm == 0 || t.a_ok1) && (pn == 0 || t.b_ok1);          // this wave's part of the tile exists
+  live_rows = t.live;
+  const bool fringe = kFringe && t.live <= 64;
+  // this wave's part of the tile exists (and is not the padding half of a fringe block row)
+  const bool mine = (pm == 0 || t.a_ok1) && (pn == 0 || t.b_ok1) && arow0 < t.live;
   // Software pipeline over NS LDS stages: K tile t lives in stage t % NS; tiles t+1 .. t+NS-2 are in flight while
   // tile t is multiplied.  Loads return in order, so "at most (NS-2) tiles' worth of loads outstanding" means tile
   // t has landed; near the end of K, when fewer tiles are in flight, the wait is for everything.
@@ -738,8 +755,11 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       }
     }
     for (int kt = 0; kt < nk; ++kt) {
-      if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kDmaPerTile) : "memory");
-      else             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // a fringe tile issues one load fewer per K tile (the chunk of rows 64..127 of the A slab)
+      static_assert(!kFringe || kCpw == 2, "a fringe tile skips exactly one A chunk per wave");
+      if (kt + 1 >= nk) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (fringe)  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kDmaPerTile - 1) : "memory");
+      else              asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kDmaPerTile) : "memory");
       __syncthreads();                             // tile kt visible to all
       const char* sa = lds + (kt & 1) * kStageBytes + pm * kPanelBytes;
       const char* sb = lds + (kt & 1) * kStageBytes + (PA + pn) * kPanelBytes;
@@ -911,6 +931,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.group_offsets = t.group_offsets;  p.row_group = t.row_group;  p.expert_order = t.expert_order;
   p.counts = t.counts;  p.sched = t.sched;
   p.tokens_per_expert = a.plain ? nullptr : t.tokens_per_expert;
+  p.token_of = a.plain ? nullptr : t.token_of;
   p.d = a.d;  p.h = a.h;  p.E = a.E;  p.hb = a.h / kBlock;  p.db = a.d / kBlock;  p.force_tile = a.force_tile;
   p.plain = a.plain;
   p.accum = a.accum;
