@@ -100,7 +100,10 @@ typedef struct {
                                             (one expert holds so many rows that its 256x256 tiles alone would
                                             outlast a balanced schedule), else 0; sched[1] = tiles per XCD patch
                                             for those products (16 when no expert is large against an XCD's
-                                            share of the rows, else 1); rest reserved                            */
+                                            share of the rows, else 1); sched[2] = 1 if DSD / DSD^T, when launched
+                                            in both tile shapes, should take the single 128x128 blocks (the macro
+                                            tiles would leave more than 15 % of their last round of CUs empty);
+                                            sched[3] reserved                                                    */
 } dmoe_topology_t;
 
 /* Buffer sizes in bytes for `cfg` (host pointers; any may be NULL).  P_max = upper bound on padded rows,

@@ -63,6 +63,7 @@ struct BsParams {
   int accum;               // 1: weight gradients are added, in fp32, to the fp32 matrix that out0 then points to
   int ka;                  // DDS: leading dimension of dense_a
   int coo;                 // 1: SDD / SDD^T take one nonzero block per workgroup, found through row_indices
+  int dual;                // 1: DSD / DSD^T were launched in both tile shapes; sched[2] says which one works
   long long* trace;        // optional (NULL = off): per work item, four 100 MHz time stamps and the K tile count
   int trace_cap;           // work items the trace buffer has room for
 };
@@ -643,6 +644,10 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       if (k == 0) p.trace[(size_t)wgi * 5 + 4] = nk;
     }
   };
+  if constexpr (kRowMajor && !kSparseOut) {
+    // launched in both tile shapes: the device-side flag says whether the single blocks (1) or the macro tiles (0) work
+    if (p.dual && p.sched[2] != (PA * PB == 1 ? 1 : 0)) return;
+  }
   if constexpr (kPipe) {
     // ---- persistent, software-pipelined loop over this workgroup's items (256x256 tiles of the token-row products)
     // One workgroup per CU walks the items blockIdx, blockIdx + grid, ...  Two things are overlapped that a
@@ -886,9 +891,20 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
   } else {
   const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
   if (row_major) {
-    bool small = (long long)a.groups_est * big_minor < 256 + (sparse_out ? 1 : 0);
+    const long long big_items = (long long)a.groups_est * big_minor;
+    bool small = big_items < 256 + (sparse_out ? 1 : 0);
+    // DSD / DSD^T have a long K (= ffn_hidden) and few tiles; with fewer than about two and a half rounds of macro
+    // tiles the last, partly filled round can cost up to half the launch (312 tiles on 256 CUs: 62 % of the CUs busy
+    // on average), and how many tiles there are depends on the routing, which the host does not know.  The single
+    // blocks deliver the same flops per CU in steady state (two workgroups per CU) and are dispatched as CUs free up,
+    // so their tail is short -- DSD^T 286 -> 211 us for 16 384 tokens over 64 experts under Zipf routing -- but they
+    // lose 15 % when the macro tiles happen to fill their rounds exactly (uniform routing).  So in that range both
+    // shapes are launched and a flag computed on the device with the routing in hand (sched[2], offsets_kernel) picks
+    // one; the other exits at once (a few microseconds).
+    bool few_rounds = !sparse_out && !small && !a.plain && big_items < 640;
     if (a.force_tile == 1) small = true;
     if (a.force_tile == 2) small = false;
+    if (a.force_tile) few_rounds = false;
     if constexpr (OP == OP_SDD) {
       if (a.act == 1 && !a.plain) {               // the tanh form of the activation is its own instantiation
         if (small) launch_variant<OP, 1, 1, 2, 8, 64, 1>(p, a.r_max, hb, s);
@@ -911,8 +927,16 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
         return;
       }
     }
-    if (small) launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
-    else       launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
+    if (few_rounds) {
+      BsParams q = p;
+      q.dual = 1;
+      launch_variant<OP, 2, 2, 2, 8>(q, a.g_max, big_minor, s);
+      launch_variant<OP, 1, 1, 2, 8>(q, a.r_max, db, s);
+    } else if (small) {
+      launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
+    } else {
+      launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
+    }
   } else {
     // the device-side flag sched[0] selects which of the two launches does the work (the other exits at once)
     launch_variant<OP, 2, 2, 2, 8>(p, a.E * ((hb + 1) / 2), big_minor, s);
@@ -937,6 +961,7 @@ void launch_bsmm(BsOp op, const BsArgs& a, hipStream_t s) {
   p.accum = a.accum;
   p.ka = a.ka;
   p.coo = a.coo;
+  p.dual = 0;
   p.trace = a.trace;  p.trace_cap = a.trace_cap;
   // Patches of 32 tiles per XCD pay off when all tiles cost the same (the products with the token dimension as
   // rows).  The weight-gradient tiles differ in K by orders of magnitude and are ordered heaviest first; the

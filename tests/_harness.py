@@ -89,7 +89,8 @@ def check_indices(gpu_topo: dict, ref: dict):
             assert r0 == first[e] + 2 * j and two == (2 * j + 1 < rows_e)
             covered += [r0] + ([r0 + 1] if two else [])
     assert covered == list(range(int(first[-1]))) and len(rg) == goff[-1]
-    assert gpu_topo["sched"][0] in (0, 1) and gpu_topo["sched"][1] in (1, 16) and not gpu_topo["sched"][2:].any()
+    assert gpu_topo["sched"][0] in (0, 1) and gpu_topo["sched"][1] in (1, 16) and gpu_topo["sched"][2] in (0, 1)
+    assert gpu_topo["sched"][3] == 0
 
 
 def rel_err(g: np.ndarray, o: np.ndarray) -> float:
