@@ -35,14 +35,14 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "sdd"): 279971430, ("xs", "dsd"): 217806029, ("xs", "sddt"): 279879066,
-    ("xs", "dstd"): 186814259, ("xs", "dsdt"): 217932800, ("xs", "ddts"): 186825114,
-    ("small_zipf1.0", "sdd"): 638619648, ("small_zipf1.0", "dsd"): 543279923, ("small_zipf1.0", "sddt"): 638298522,
-    ("small_zipf1.0", "dstd"): 1004661350, ("small_zipf1.0", "dsdt"): 542840422, ("small_zipf1.0", "ddts"): 973299712,
-    ("medium_zipf1.2_top2", "sdd"): 2359846298, ("medium_zipf1.2_top2", "dsd"): 2597350195, ("medium_zipf1.2_top2", "sddt"): 2363067187,
-    ("medium_zipf1.2_top2", "dstd"): 2777749094, ("medium_zipf1.2_top2", "dsdt"): 2618416742, ("medium_zipf1.2_top2", "ddts"): 2777421619,
-    ("large_expert_top2", "sdd"): 17531976294, ("large_expert_top2", "dsd"): 13474023219, ("large_expert_top2", "sddt"): 17692413133,
-    ("large_expert_top2", "dstd"): 13536413901, ("large_expert_top2", "dsdt"): 17553352704, ("large_expert_top2", "ddts"): 13459670016,
+    ("xs", "sdd"): 260430029, ("xs", "dsd"): 208423936, ("xs", "sddt"): 260268442,
+    ("xs", "dstd"): 186820403, ("xs", "dsdt"): 210293146, ("xs", "ddts"): 186809958,
+    ("small_zipf1.0", "sdd"): 683923456, ("small_zipf1.0", "dsd"): 880553984, ("small_zipf1.0", "sddt"): 681490842,
+    ("small_zipf1.0", "dstd"): 1008218522, ("small_zipf1.0", "dsdt"): 809673933, ("small_zipf1.0", "ddts"): 997520384,
+    ("medium_zipf1.2_top2", "sdd"): 2504606106, ("medium_zipf1.2_top2", "dsd"): 2566750413, ("medium_zipf1.2_top2", "sddt"): 2545631846,
+    ("medium_zipf1.2_top2", "dstd"): 2780994560, ("medium_zipf1.2_top2", "dsdt"): 2596879770, ("medium_zipf1.2_top2", "ddts"): 2765251994,
+    ("large_expert_top2", "sdd"): 25869003366, ("large_expert_top2", "dsd"): 14334838579, ("large_expert_top2", "sddt"): 25285424947,
+    ("large_expert_top2", "dstd"): 13339720294, ("large_expert_top2", "dsdt"): 14079246336, ("large_expert_top2", "ddts"): 15054653440,
 }
 
 
