@@ -32,7 +32,7 @@ namespace dmoe {
 // a slab is 128 x BK bf16 = 256*BK bytes either way round, a stage is four slabs (A0 A1 B0 B1).
 constexpr int kBlockElems = kBlock * kBlock;  // 16384 values per sparse block
 constexpr int kPatch = 32;                    // macro tiles that should run together on one XCD (one per CU)
-constexpr int kMaxGradGrid = 4096;            // cap on the grid of a weight-gradient launch (multiple of 8 * kPatch)
+constexpr int kMaxGradGrid = 8192;            // cap on the grid of a weight-gradient launch (multiple of 8 * kPatch)
 constexpr int kPersistGrid = 256;             // workgroups of a persistent launch: one per CU (a multiple of 8 * kPatch)
 constexpr int kPatchSlack = 5;                // tolerated XCD imbalance, in 64ths, when the patch size is chosen
 
