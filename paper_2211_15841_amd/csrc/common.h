@@ -34,17 +34,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // Standard normal CDF Phi(v) and density phi(v), fp32.  erfc through the five-term rational-exponential
 // approximation of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7), arranged so that the small tail is
 // computed directly rather than as 1 - (almost 1).
+// The SDD epilogue is bound by the vector ALU, so the constants are folded (the 1/sqrt(2) into the rational argument,
+// the 1/2 into the polynomial, the -1/2 and log2(e) into one factor in front of the hardware's base-2 exponential)
+// and the two branches of the CDF are joined with a sign copy: Phi(v) = 1/2 + sign(v) (1/2 - Phi(-|v|)).
 __device__ __forceinline__ void normal_cdf_pdf(float v, float& cdf, float& pdf) {
-  const float az = fabsf(v) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(az, 0.3275911f, 1.0f));
-  float poly = fmaf(t, 1.061405429f, -1.453152027f);
-  poly = fmaf(poly, t, 1.421413741f);
-  poly = fmaf(poly, t, -0.284496736f);
-  poly = fmaf(poly, t, 0.254829592f);
+  const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(v), 0.3275911f * 0.70710678118654752f, 1.0f));
+  float poly = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  poly = fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = fmaf(poly, t, 0.5f * 0.254829592f);
   poly *= t;
-  const float ex = __expf(-0.5f * v * v);
-  const float tail = 0.5f * poly * ex;              // = Phi(-|v|)
-  cdf = v < 0.0f ? tail : 1.0f - tail;
+  const float ex = __builtin_amdgcn_exp2f(v * v * (-0.5f * 1.4426950408889634f));   // exp(-v^2 / 2)
+  const float half_minus_tail = fmaf(-poly, ex, 0.5f);                                // 1/2 - Phi(-|v|), in [0, 1/2]
+  cdf = 0.5f + __builtin_copysignf(half_minus_tail, v);
   pdf = ex * 0.39894228040143268f;
 }
 // The tanh form of GELU, 0.5 v (1 + tanh(u)) with u = sqrt(2/pi) (v + 0.044715 v^3), written the same way: `cdf` is
