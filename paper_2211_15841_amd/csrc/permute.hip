@@ -291,7 +291,7 @@ static int dwr_chunk_tokens(const dmoe_config& c) {
     if (((c.num_tokens + tok - 1) / tok) * col_tiles >= 256) return tok;
   return 64;
 }
-__global__ void __launch_bounds__(256) dwr_mfma_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dlogits,
+__global__ void __launch_bounds__(256, 3) dwr_mfma_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dlogits,
                                                        float* __restrict__ partials, int T, int d, int E, int kDwrTok) {
   __shared__ __attribute__((aligned(16))) char xs[16384];
   __shared__ __attribute__((aligned(16))) char hs[16384];
