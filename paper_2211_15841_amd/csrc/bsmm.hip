@@ -866,7 +866,9 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
 // 256x128 tiles with three LDS stages (-15..20 %), K = 32 per stage with three to five stages (-5..8 %; -20 % on the
 // 128x128 tile, where 64-byte row pieces double the number of memory requests), deeper pipelines on the 128x128 tile
 // at one workgroup per CU (no faster per K tile, and one workgroup per CU quantises worse), four extra waves that
-// only issue the loads (-15 %), and staging through registers (global_load + ds_write, -8..12 %).  A wave can issue
+// only issue the loads (-15 %), staging through registers (global_load + ds_write, -8..12 %), and four waves of
+// 128x128 on the 256x256 tile with the accumulators in the accumulation registers (a third less LDS read traffic,
+// but one wave per SIMD: K loop -7 %, epilogues -30..60 %; LDS read bandwidth is not what bounds the loop).  A wave can issue
 // one direct-to-LDS load per ~120 cycles (a CU one per ~20, i.e. ~50 B/clk), which is why the loads are spread over
 // the first two K steps of the MFMA loop.  The products are bound by operand delivery into LDS, not by load latency, so
 // intensity wins over pipeline depth.

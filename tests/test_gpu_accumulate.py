@@ -94,3 +94,37 @@ def test_two_micro_batches(cfg, tile_mode):
                 check_values(k + " (joined)", got[k] - start[k], gj[k])
     finally:
         dm.dmoe_set_tile_mode(0)
+
+
+@pytest.mark.parametrize("pad", [0, 1], ids=["drop", "drop_and_pad"])
+def test_accumulate_with_token_dropping(pad):
+    """The token-dropping variant (Section 2.2) through the accumulating entry point: dropped assignments add nothing,
+    and one micro-batch into zeros rounds to dmoe_backward's gradients bit for bit."""
+    cfg = small_config("acc_capacity", T=500, d=256, h=256, E=5, k=2, normalize_topk=1, zipf_s=1.2, seed=311,
+                       expert_capacity=150, pad_to_capacity=pad)
+    inp = make_inputs(cfg)
+    d, h, E = cfg.d_model, cfg.ffn_hidden, cfg.num_experts
+    ws = dm.Workspace(cfg.num_tokens, d, h, E, cfg.top_k, cfg.normalize_topk, expert_capacity=cfg.expert_capacity,
+                      pad_to_capacity=pad)
+    x, dy = to_dev(inp["x"]), to_dev(inp["dy"])
+    w = {k: to_dev(inp[k]) for k in ("w_router", "w1", "w2")}
+    bias = torch.from_numpy(inp["router_bias"]).cuda() if inp.get("router_bias") is not None else None
+    ws.topology(x, w["w_router"], bias)
+    ws.forward(x, w["w1"], w["w2"])
+    dx, dwr, dw1, dw2 = [t.clone() for t in ws.backward(x, w["w_router"], w["w1"], w["w2"], dy)]
+    acc = {"dw_router": torch.zeros(d, E, device="cuda"), "dw1": torch.zeros(d, E * h, device="cuda"),
+           "dw2": torch.zeros(E * h, d, device="cuda")}
+    dx_acc = ws.backward_accumulate(x, w["w_router"], w["w1"], w["w2"], dy, acc["dw_router"], acc["dw1"],
+                                    acc["dw2"]).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(dx_acc.view(torch.int16), dx.view(torch.int16))
+    assert torch.equal(acc["dw1"].to(torch.bfloat16).view(torch.int16), dw1.view(torch.int16))
+    assert torch.equal(acc["dw2"].to(torch.bfloat16).view(torch.int16), dw2.view(torch.int16))
+    assert torch.equal(acc["dw_router"], dwr)
+    ref = run_oracle_indices(cfg, inp)
+    keep = orc.capacity_keep_mask(ref["expert_idx"], E, cfg.expert_capacity)
+    assert not keep.all(), "the case is meant to drop something"
+    g = orc.backward(inp["x"], inp["w_router"], inp["w1"], inp["w2"], inp["dy"], ref["expert_idx"], ref["weights"],
+                     ref["probs"], h, cfg.normalize_topk, keep_mask=keep)
+    for k in ("dw1", "dw2", "dw_router"):
+        check_values(k, acc[k].cpu().numpy().astype(np.float64), g[k])
