@@ -254,8 +254,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the register-only MFMA peak probe (keeps its kernel out of rocprofv3 summaries)")
-    ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2),
-                    help="0: the library's own tile choice (default); 1 / 2: force 128x128 / 256x256 tiles (experiments)")
+    ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2, 3),
+                    help="0: the library's own tile choice (default); 1 / 2: force 128x128 / 256x256 tiles; 3: 256x256 tiles on the "
+                         "two-stage loop instead of the slab ring (experiments)")
     ap.add_argument("--accumulate", action="store_true",
                     help="time dmoe_backward_accumulate (fp32 weight-gradient accumulators) instead of dmoe_backward; "
                          "a variant for context, not the headline step")

@@ -197,8 +197,9 @@ DMOE_API int dmoe_debug_trace(void *buffer, size_t bytes, int stage);
 DMOE_API int dmoe_set_stage_events(void *events);
 
 /* Tile shape of the block-sparse products: 0 = chosen from the configuration (default), 1 = one 128x128 block per
- * workgroup, 2 = 256x256 macro tiles (2x2 blocks).  Process-wide; results are identical, only speed differs.
- * Meant for tests and tuning.                                                                                  */
+ * workgroup, 2 = 256x256 macro tiles (2x2 blocks), 3 = 256x256 macro tiles whose token-row products run on two LDS
+ * stages instead of the five-stage slab ring (kept so that the two loops can be measured against each other).
+ * Process-wide; results are identical, only speed differs.  Meant for tests and tuning.                        */
 DMOE_API int dmoe_set_tile_mode(int mode);
 
 /* ---- General block-sparse products (Sections 4.2, 5.1) ---------------------------------------------------------

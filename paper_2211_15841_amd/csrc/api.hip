@@ -466,7 +466,7 @@ int dmoe_set_stage_events(void* events) {
 }
 
 int dmoe_set_tile_mode(int mode) {
-  if (mode < 0 || mode > 2) return fail(DMOE_EINVAL, "tile mode must be 0 (automatic), 1 (128x128) or 2 (256x256)");
+  if (mode < 0 || mode > 3) return fail(DMOE_EINVAL, "tile mode must be 0 (automatic), 1 (128x128), 2 (256x256) or 3 (256x256 on two LDS stages)");
   g_force_tile.store(mode, std::memory_order_relaxed);
   return DMOE_OK;
 }

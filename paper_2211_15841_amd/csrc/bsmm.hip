@@ -56,7 +56,7 @@ struct BsParams {
   const int32_t* tokens_per_expert;   // dMoE topologies only (NULL for a general mask): lets the weight gradients skip padding
   const int32_t* token_of;            // dMoE topologies only: tells a block row whose second half is all padding (a fringe)
   int d, h, E, hb, db;
-  int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256
+  int force_tile;          // 0: device-side choice for the weight gradients, 1: 128x128, 2: 256x256, 3: 256x256 on two stages
   int patch;               // > 0: tiles per XCD patch (see patch_item); <= 0: balanced_patch with slack -patch
   int items;               // work items of this launch (weight gradients: may exceed the grid)
   int plain;               // 1: SDD / SDD^T without their fused epilogues (general block-sparse products)
@@ -143,6 +143,9 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // The 256x256 tiles of the token-row products run as a persistent, software-pipelined loop over the items of a
   // workgroup (see the end of the kernel); everything else takes one item at a time.
   constexpr bool kPipe = kRowMajor && PA == 2 && PB == 2 && NS == 2 && NW == 8;
+  // The same loop over a slab ring: three stages for the A slabs, two for the B slabs (160 KB, all of LDS).  The A
+  // slabs of a K tile are requested two tiles ahead and the B slabs one, so 96 KB instead of 64 KB are in flight.
+  constexpr bool kRing = kRowMajor && PA == 2 && PB == 2 && NS == 3 && NW == 8;
   // tiles of one block row of the token-row products of the layer skip the padding half of a fringe block row
   constexpr bool kFringe = kRowMajor && PA == 1 && NS == 2 && NW == 8 && BK == 64 && OP <= OP_DDTS;
   constexpr int kEpRows = MI >= 2 ? 64 : 32;        // rows of the wave's tile that pass through its staging tile at a time
@@ -288,6 +291,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     // in front of the v_readlane of every iteration
     asm volatile("" : "+v"(t.ix0), "+v"(t.ix1), "+v"(t.ix2));
   };
+  bool refill_ok = true;             // cleared around a second visit to a K tile whose indices are already in registers
   auto slab_ptrs = [&](TileState& t, int kt) {
     if constexpr (OP == OP_SDD) {
       a0 = p.dense_a + (size_t)t.r0 * kBlock * d + kt * BK;
@@ -314,7 +318,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       // Y = X S^T (or X^T S^T): output block-column r is block-row r of S; its blocks (r, col), walked in the primary
       // order, are the B operand as they lie in memory ([n][k], k contiguous); X supplies the block-column col
       const int kb = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, kb);
       const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
       if constexpr (OP == OP_DDST) a0 = p.dense_a + (size_t)t.jd0 * kBlock * lda + (size_t)col * kBlock + half * BK;
       else                         a0 = p.dense_a + ((size_t)col * kBlock + half * BK) * lda + (size_t)t.jd0 * kBlock;
@@ -324,7 +328,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     } else if constexpr (OP == OP_DSTDT) {
       // Y = S^T X^T with X given as [D, M]: as DS^TD, but the dense operand has its K index contiguous
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, i);
       const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
       const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
       a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
@@ -333,7 +337,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       b1 = b0;
     } else if constexpr (OP == OP_DSD) {
       const int kb = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, kb);
       const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
       a0 = p.sparse_in + (size_t)(t.first0 + kb) * kBlockElems + half * BK;
       a1 = p.sparse_in + (size_t)(t.first1 + kb) * kBlockElems + half * BK;
@@ -341,7 +345,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       b1 = b0 + (t.b_ok1 ? kBlock : 0);
     } else if constexpr (OP == OP_DSDT) {
       const int kb = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, kb);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, kb);
       const int col = __builtin_amdgcn_readlane(t.ix0, kb & 63);
       a0 = p.sparse_in + (size_t)(t.first0 + kb) * kBlockElems + half * BK;
       a1 = p.sparse_in + (size_t)(t.first1 + kb) * kBlockElems + half * BK;
@@ -349,7 +353,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       b1 = b0 + (t.b_ok1 ? (size_t)kBlock * ldw : 0);
     } else if constexpr (OP == OP_DSTD) {
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, i);
       const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
       const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
       a0 = p.sparse_in + (size_t)blk0 * kBlockElems + half * BK * kBlock;
@@ -359,7 +363,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     } else if constexpr (OP == OP_DDS) {
       // Y = X S: for the blocks (row, c) of column c, in the order of the transposed lists, X[:, row] times the block
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, i);
       const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
       const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
       a0 = p.dense_a + (size_t)t.jd0 * kBlock * p.ka + (size_t)row * kBlock + half * BK;
@@ -368,7 +372,7 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
       b1 = p.sparse_in + (size_t)blk1 * kBlockElems + half * BK * kBlock;
     } else {  // OP_DDTS
       const int i = kt / kSub, half = kt % kSub;
-      if ((kt & (64 * kSub - 1)) == 0) refill(t, i);
+      if ((kt & (64 * kSub - 1)) == 0 && refill_ok) refill(t, i);
       const int blk0 = __builtin_amdgcn_readlane(t.ix0, i & 63), blk1 = __builtin_amdgcn_readlane(t.ix1, i & 63);
       const int row = __builtin_amdgcn_readlane(t.ix2, i & 63);
       a0 = p.dense_a + ((size_t)row * kBlock + half * BK) * d + (size_t)t.jd0 * kBlock;
@@ -648,6 +652,111 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
     // launched in both tile shapes: the device-side flag says whether the single blocks (1) or the macro tiles (0) work
     if (p.dual && p.sched[2] != (PA * PB == 1 ? 1 : 0)) return;
   }
+  if constexpr (kRing) {
+    // "far" operand: three stages, requested two K tiles ahead; "near" operand: two stages, one tile ahead.  The
+    // weights (B, rows hundreds of KB apart) are the far operand, except in DSD^T, which measured better with the
+    // blocks of dH far (-3 % on that product; the other three gain 0-2 % from the weights being far).
+    constexpr bool kFarB = OP != OP_DSDT;
+    static_assert(PA == PB, "the two rings hold slabs of one size");
+    constexpr int kStage = PA * kPanelBytes, kNearBase = 3 * kStage;
+    constexpr int kDmaFar = PA * kCpw;                             // loads per wave for the far slabs of one K tile
+    auto issue_ab = [&](bool b_slabs, uint32_t base) {
+      const uint32_t s = __builtin_amdgcn_readfirstlane(lds_base + base + wave * 1024);
+#pragma unroll
+      for (int i = 0; i < kCpw; ++i) {
+        dma16(b_slabs ? b0 : a0, b_slabs ? ob[i] : oa[i], s + NW * 1024 * i);
+        dma16(b_slabs ? b1 : a1, b_slabs ? ob[i] : oa[i], s + kPanelBytes + NW * 1024 * i);
+      }
+    };
+    auto issue_far = [&](int st) { issue_ab(kFarB, st * kStage); };
+    auto issue_near = [&](int st) { issue_ab(!kFarB, kNearBase + st * kStage); };
+    const int items = ((majors_live + 3) / 4 * 4 * nminor + 8 * kPatch - 1) / (8 * kPatch) * (8 * kPatch);
+    TileState cur, nxt;
+    int wgi = blockIdx.x;
+    bool have = false;
+    for (; wgi < items; wgi += gridDim.x)
+      if (decode(wgi, cur)) { have = true; break; }
+    int gf = 0, gn = 0;                 // stages of the K tile being multiplied: far ring of three, near ring of two
+    bool far_ahead = false;             // the far slabs of the next K tile were requested after the near slabs of this one
+    if (have) {                         // every item has at least two K tiles
+      slab_ptrs(cur, 0);
+      issue_far(0);
+      issue_near(0);
+      slab_ptrs(cur, 1);
+      issue_far(1);
+      far_ahead = true;
+    }
+    while (have) {
+      bool have_next = false;
+      int nwgi = wgi + gridDim.x;
+      for (; nwgi < items; nwgi += gridDim.x)
+        if (decode(nwgi, nxt)) { have_next = true; break; }
+      const int nk = cur.nk;
+      const bool mine = (pm == 0 || cur.a_ok1) && (pn == 0 || cur.b_ok1);
+      clear_acc();
+      Frags f0, f1;
+      stamp(wgi, 0, nk);
+      for (int kt = 0; kt < nk; ++kt) {
+        // K tile kt needs its far slabs (requested two tiles ago) and its near slabs (one tile ago); the far slabs of the
+        // next K tile, requested after those, may stay in flight (loads retire in order)
+        if (far_ahead) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kDmaFar) : "memory");
+        else           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();            // K tile kt visible; every wave is done with the tile before it (and its staging tile)
+        if (kt == 0) stamp(wgi, 1, nk);
+        const char* sfar = lds + gf * kStage;
+        const char* snear = lds + kNearBase + gn * kStage;
+        const char* sa = (kFarB ? snear : sfar) + pm * kPanelBytes;
+        const char* sb = (kFarB ? sfar : snear) + pn * kPanelBytes;
+        if (mine) read_frags(f0, sa, sb, 0);
+        // the near slabs of the next K tile go where those of the previous one were, the far slabs of the one after
+        // next where the previous far slabs were; near the end of an item both belong to the next item
+        const bool one = kt + 1 < nk || have_next;
+        const bool two = kt + 2 < nk || have_next;
+        if (one) {
+          if (kt + 1 < nk) {
+            slab_ptrs(cur, kt + 1);
+          } else {                  // the far slabs of this K tile were requested an iteration ago: its indices are there
+            refill_ok = false;
+            slab_ptrs(nxt, 0);
+            refill_ok = true;
+          }
+          issue_near(gn ^ 1);
+        }
+        if (mine) {
+          if (kt > 0) mfma_frags(f1);                            // K step 3 of the previous K tile
+          read_frags(f1, sa, sb, 1);
+        }
+        if (two) {
+          if (kt + 2 < nk) slab_ptrs(cur, kt + 2);
+          else             slab_ptrs(nxt, kt + 2 - nk);
+          issue_far(gf == 0 ? 2 : gf - 1);                        // (gf + 2) % 3
+        }
+        far_ahead = two;
+        if (mine) {
+          mfma_frags(f0);
+          read_frags(f0, sa, sb, 2);
+          mfma_frags(f1);
+          read_frags(f1, sa, sb, 3);
+          mfma_frags(f0);
+        }
+        if (kt + 1 < nk) {
+          gf = gf == 2 ? 0 : gf + 1;
+          gn ^= 1;
+        }
+      }
+      if (mine) mfma_frags(f1);
+      stamp(wgi, 2, nk);
+      __syncthreads();              // every wave has read the last K tile: its slabs are free for the staging tiles
+      // waves 0-3 stage in the far slabs of the last K tile, waves 4-7 in its near slabs (32 KB each)
+      if (mine) epilogue(cur, lds + (wave < 4 ? gf * kStage + wave * kEpBytes : kNearBase + gn * kStage + (wave - 4) * kEpBytes));
+      stamp(wgi, 3, nk);
+      gf = gf == 2 ? 0 : gf + 1;
+      gn ^= 1;
+      cur = nxt;
+      wgi = nwgi;
+      have = have_next;
+    }
+  } else
   if constexpr (kPipe) {
     // ---- persistent, software-pipelined loop over this workgroup's items (256x256 tiles of the token-row products)
     // One workgroup per CU walks the items blockIdx, blockIdx + grid, ...  Two things are overlapped that a
@@ -836,7 +945,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
 
 template <int OP, int PA, int PB, int NS, int NW, int BK = 64, int ACT = 0>
 static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_t s) {
-  constexpr int kLds = NS * (PA + PB) * 256 * BK;
+  constexpr bool ring = PA == 2 && PB == 2 && NS == 3 && NW == 8;       // three A stages and two B stages
+  constexpr int kLds = ring ? (3 * PA + 2 * PB) * 256 * BK : NS * (PA + PB) * 256 * BK;
   // raise the dynamic-LDS limit of this instantiation once per process (thread-safe; a failure is reported by every
   // later launch of the variant instead of surfacing as an unexplained launch error)
   static std::once_flag once;
@@ -857,7 +967,7 @@ static void launch_variant(const BsParams& p, int majors, int nminor, hipStream_
   constexpr bool grad = OP == OP_DSTD || OP == OP_DDTS || OP == OP_DDS || OP == OP_DSTDT;
   if (grad && grid > kMaxGradGrid) grid = kMaxGradGrid;
   // the 256x256 tiles of the token-row products run as a persistent loop: one workgroup per CU (128 KB of LDS each)
-  constexpr bool pipe = !grad && PA == 2 && PB == 2 && NS == 2 && NW == 8;
+  constexpr bool pipe = !grad && PA == 2 && PB == 2 && (NS == 2 || NS == 3) && NW == 8;
   if (pipe && grid > kPersistGrid) grid = kPersistGrid;
   hipLaunchKernelGGL((bsmm_kernel<OP, PA, PB, NS, NW, BK, ACT>), dim3(grid), dim3(NW * 64), kLds, s, q);
 }
@@ -892,7 +1002,7 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
     else                                           launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, db, s);
   } else {
   const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
-  if (row_major) {
+  if constexpr (row_major) {
     const long long big_items = (long long)a.groups_est * big_minor;
     bool small = big_items < 256 + (sparse_out ? 1 : 0);
     // DSD / DSD^T have a long K (= ffn_hidden) and few tiles; with fewer than about two and a half rounds of macro
@@ -905,12 +1015,14 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
     // one; the other exits at once (a few microseconds).
     bool few_rounds = !sparse_out && !small && !a.plain && big_items < 640;
     if (a.force_tile == 1) small = true;
-    if (a.force_tile == 2) small = false;
+    if (a.force_tile >= 2) small = false;
+    const bool two_stage = a.force_tile == 3;       // macro tiles on two LDS stages instead of the slab ring
     if (a.force_tile) few_rounds = false;
     if constexpr (OP == OP_SDD) {
       if (a.act == 1 && !a.plain) {               // the tanh form of the activation is its own instantiation
-        if (small) launch_variant<OP, 1, 1, 2, 8, 64, 1>(p, a.r_max, hb, s);
-        else       launch_variant<OP, 2, 2, 2, 8, 64, 1>(p, a.g_max, big_minor, s);
+        if (small)          launch_variant<OP, 1, 1, 2, 8, 64, 1>(p, a.r_max, hb, s);
+        else if (two_stage) launch_variant<OP, 2, 2, 2, 8, 64, 1>(p, a.g_max, big_minor, s);
+        else                launch_variant<OP, 2, 2, 3, 8, 64, 1>(p, a.g_max, big_minor, s);
         return;
       }
     }
@@ -932,12 +1044,13 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
     if (few_rounds) {
       BsParams q = p;
       q.dual = 1;
-      launch_variant<OP, 2, 2, 2, 8>(q, a.g_max, big_minor, s);
+      launch_variant<OP, 2, 2, 3, 8>(q, a.g_max, big_minor, s);
       launch_variant<OP, 1, 1, 2, 8>(q, a.r_max, db, s);
     } else if (small) {
       launch_variant<OP, 1, 1, 2, 8>(p, a.r_max, sparse_out ? hb : db, s);
     } else {
-      launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
+      if (two_stage) launch_variant<OP, 2, 2, 2, 8>(p, a.g_max, big_minor, s);
+      else           launch_variant<OP, 2, 2, 3, 8>(p, a.g_max, big_minor, s);
     }
   } else {
     // the device-side flag sched[0] selects which of the two launches does the work (the other exits at once)

@@ -94,7 +94,7 @@ struct BsArgs {
   int d, h, E;
   int g_max, r_max;        // upper bounds on the number of row groups / block rows
   int groups_est;          // T*k/256: row groups if the routing were perfectly packed (tile-size heuristic)
-  int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles (tests)
+  int force_tile;          // 0: heuristic, 1: 128x128 tiles, 2: 256x256 macro tiles, 3: the same on two LDS stages (tests)
   int plain;               // 1: no fused epilogue (SDD writes the product to out0, SDD^T does not multiply by sparse_in)
   int accum;               // 1: DS^TD / DD^TS add their result, in fp32, to the fp32 matrix at out0
   int ka;                  // DDS and the products of Section 5.1.1 beyond the layer's: 128 * block rows of S

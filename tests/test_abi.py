@@ -94,9 +94,10 @@ def test_bind_and_calls_validate_pointers_without_launching():
 def test_tile_mode_is_validated():
     dm.dmoe_set_tile_mode(1)
     dm.dmoe_set_tile_mode(2)
+    dm.dmoe_set_tile_mode(3)
     dm.dmoe_set_tile_mode(0)
     with pytest.raises(dm.DMoEError, match="tile mode"):
-        dm.dmoe_set_tile_mode(3)
+        dm.dmoe_set_tile_mode(4)
 
 
 def test_general_products_validate_their_arguments():

@@ -92,10 +92,11 @@ def test_two_runs_are_bitwise_identical():
         assert np.array_equal(val, b["topo"][key]), key
 
 
-@pytest.mark.parametrize("mode", [1, 2], ids=["tiles_128", "tiles_256"])
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["tiles_128", "tiles_256", "tiles_256_two_stages"])
 def test_both_tile_shapes_give_the_same_answers(mode):
-    """The block-sparse products have a 128x128 and a 256x256 tiling; force each one on cases with odd block counts,
-    empty experts and a dominant expert (the automatic choice is covered by every other test)."""
+    """The block-sparse products have a 128x128 and a 256x256 tiling, the latter with a slab-ring and a two-stage loop;
+    force each one on cases with odd block counts, empty experts and a dominant expert (the automatic choice is covered
+    by every other test)."""
     import paper_2211_15841_amd as dm
     dm.dmoe_set_tile_mode(mode)
     try:
@@ -107,7 +108,7 @@ def test_both_tile_shapes_give_the_same_answers(mode):
         dm.dmoe_set_tile_mode(0)
 
 
-@pytest.mark.parametrize("tile_mode", [1, 2], ids=["tiles_128", "tiles_256"])
+@pytest.mark.parametrize("tile_mode", [1, 2, 3], ids=["tiles_128", "tiles_256", "tiles_256_two_stages"])
 def test_tanh_form_of_the_activation(tile_mode):
     """activation = 1: the fused epilogue of SDD (activation and its derivative) in the tanh form.
 
