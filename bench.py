@@ -35,14 +35,14 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "sdd"): 260430029, ("xs", "dsd"): 208423936, ("xs", "sddt"): 260268442,
-    ("xs", "dstd"): 186820403, ("xs", "dsdt"): 210293146, ("xs", "ddts"): 186809958,
-    ("small_zipf1.0", "sdd"): 683923456, ("small_zipf1.0", "dsd"): 880553984, ("small_zipf1.0", "sddt"): 681490842,
-    ("small_zipf1.0", "dstd"): 1008218522, ("small_zipf1.0", "dsdt"): 809673933, ("small_zipf1.0", "ddts"): 997520384,
-    ("medium_zipf1.2_top2", "sdd"): 2504606106, ("medium_zipf1.2_top2", "dsd"): 2566750413, ("medium_zipf1.2_top2", "sddt"): 2545631846,
-    ("medium_zipf1.2_top2", "dstd"): 2780994560, ("medium_zipf1.2_top2", "dsdt"): 2596879770, ("medium_zipf1.2_top2", "ddts"): 2765251994,
-    ("large_expert_top2", "sdd"): 25869003366, ("large_expert_top2", "dsd"): 14334838579, ("large_expert_top2", "sddt"): 25285424947,
-    ("large_expert_top2", "dstd"): 13339720294, ("large_expert_top2", "dsdt"): 14079246336, ("large_expert_top2", "ddts"): 15054653440,
+    ("xs", "dsdt"): 210096333, ("xs", "sdd"): 260350976, ("xs", "ddts"): 186823270,
+    ("xs", "dstd"): 186819994, ("xs", "dsd"): 208352666, ("xs", "sddt"): 260302643,
+    ("small_zipf1.0", "ddts"): 987207885, ("small_zipf1.0", "dstd"): 1006448026, ("small_zipf1.0", "sdd"): 681239142,
+    ("small_zipf1.0", "dsdt"): 806032589, ("small_zipf1.0", "dsd"): 871372595, ("small_zipf1.0", "sddt"): 687388467,
+    ("medium_zipf1.2_top2", "sdd"): 2524065178, ("medium_zipf1.2_top2", "ddts"): 2754489549, ("medium_zipf1.2_top2", "dstd"): 2764244787,
+    ("medium_zipf1.2_top2", "sddt"): 2785978982, ("medium_zipf1.2_top2", "dsdt"): 2632176640, ("medium_zipf1.2_top2", "dsd"): 2608725402,
+    ("large_expert_top2", "sdd"): 28711848755, ("large_expert_top2", "dsd"): 16043077427, ("large_expert_top2", "dsdt"): 15031072973,
+    ("large_expert_top2", "sddt"): 29492886323, ("large_expert_top2", "dstd"): 13472427827, ("large_expert_top2", "ddts"): 15239494042,
 }
 
 
