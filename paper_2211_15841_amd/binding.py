@@ -8,7 +8,8 @@ from ctypes import c_int32, c_size_t, c_void_p, c_char_p, POINTER, byref
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdmoe.so")
+# DMOE_LIBRARY names another build of the same library (the host-sanitized one that the ABI tests load in a child process)
+LIB_PATH = os.environ.get("DMOE_LIBRARY") or os.path.join(_HERE, "libdmoe.so")
 
 STAGE_NAMES = ["router", "sort", "topology", "gather", "sdd", "dsd", "scatter", "bwd_gather", "sddt", "dstd",
                "dsdt", "ddts", "router_bwd"]

@@ -54,6 +54,28 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+HOST_CHECKED_LIB = os.path.join(BUILD, "libdmoe_hostcheck.so")
+# the host pass of the two C-ABI source files under the undefined-behaviour sanitizer in trapping form (no runtime
+# library needed: a signed overflow, an out-of-bounds index of a fixed array, a bad shift or a misaligned access in the
+# size and layout arithmetic ends the process); device code is compiled as always
+HOST_CHECK_FLAGS = ["-Xarch_host", "-fsanitize=undefined,bounds", "-Xarch_host", "-fsanitize-trap=all",
+                    "-Xarch_host", "-fno-sanitize=function,vptr"]
+
+
+def build_host_checked() -> str:
+    """libdmoe_hostcheck.so: api.hip and bsmm_api.hip with their host code sanitized, the kernel files as in libdmoe.so."""
+    os.makedirs(BUILD, exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        checked = src in ("api.hip", "bsmm_api.hip")
+        obj = os.path.join(BUILD, src.replace(".hip", ".hostcheck.o" if checked else ".o"))
+        if checked or not os.path.exists(obj):
+            _run([HIPCC, *FLAGS, *(HOST_CHECK_FLAGS if checked else []), "-c", os.path.join(CSRC, src), "-o", obj])
+        objs.append(obj)
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", HOST_CHECKED_LIB, *objs])
+    return HOST_CHECKED_LIB
+
+
 VENDOR_BENCH = os.path.join(BUILD, "bench_vendor_bmm")
 
 

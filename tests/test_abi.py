@@ -3,6 +3,8 @@ buffers as documented, and turns invalid arguments into error codes before anyth
 import ctypes
 import os
 import re
+import subprocess
+import sys
 
 import pytest
 
@@ -199,3 +201,41 @@ def test_sizes_cover_the_worst_routing(shape):
         assert P <= s["P_max"] and R * hb <= s["nnz_max"]
         assert groups <= (s["P_max"] // 128 + min(E, F) + 1) // 2
         assert len(token_of) == P and row_of.max() < P
+
+
+def test_extreme_sizes_give_an_error_or_a_size_never_a_crash():
+    """The size arithmetic with every dimension at its extremes: each call returns sizes or a clean DMOE_EINVAL."""
+    big = 2 ** 31 - 1
+    seen_ok = seen_err = 0
+    for T in (1, 127, 2 ** 23, 2 ** 24 - 1, 2 ** 24, big):
+        for d, h in ((128, 128), (128, big // 128 * 128), (big // 128 * 128, 128), (2 ** 20, 2 ** 20), (16384, 65536)):
+            for E, k in ((1, 1), (256, 1), (256, 8), (64, 4)):
+                for cap, pad in ((0, 0), (1, 1), (big, 0), (big, 1)):
+                    try:
+                        s = dm.dmoe_sizes(_cfg(T=T, d=d, h=h, E=E, k=k, cap=cap, pad=pad))
+                    except dm.DMoEError as e:
+                        assert "dmoe error -1" in str(e)
+                        seen_err += 1
+                        continue
+                    seen_ok += 1
+                    assert s["P_max"] % 128 == 0 and 0 < s["P_max"] < 2 ** 31 and 0 < s["nnz_max"] < 2 ** 31
+                    assert all(s[key] % 256 == 0 and s[key] > 0 for key in ("topology_bytes", "saved_bytes", "scratch_bytes"))
+    assert seen_ok and seen_err
+    for rows, cols, nnz in ((1, 1, 0), (big, 1, 1), (1, big, big), (big, big, big), (46340, 46341, 1)):
+        try:
+            assert dm.dmoe_bsmm_sizes(rows, cols, nnz) % 256 == 0
+        except dm.DMoEError as e:
+            assert "dmoe error" in str(e)
+
+
+@pytest.mark.skipif(os.environ.get("DMOE_LIBRARY") is not None, reason="already running against another build")
+def test_host_code_under_the_undefined_behaviour_sanitizer():
+    """The ABI tests once more, in a child process, against a build whose host code traps on undefined behaviour (signed
+    overflow, out-of-bounds array index, misaligned access, bad shift) in the size, layout and validation code."""
+    from paper_2211_15841_amd import build
+    lib = build.build_host_checked()
+    env = dict(os.environ, DMOE_LIBRARY=lib)
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-q", "-x", "-m", "not gpu", "-p",
+                        "no:cacheprovider", "-k", "not missing_library"], env=env, cwd=ROOT, capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout[-2000:], r.stderr[-2000:])
+    assert " passed" in r.stdout
