@@ -153,7 +153,8 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   extern __shared__ __attribute__((aligned(1024))) char lds[];   // [NS stages][A slabs, B slabs]
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  // the wave number is the same for all lanes: saying so keeps everything derived from it in scalar registers
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wq = wave / WB;                         // which 128x128 block of the tile: A panel pm, B panel pn
   const int pm = wq / PB, pn = wq % PB;
   const int arow0 = ((wave % WB) >> 1) * (32 * MI);  // first row of the wave inside its A panel
@@ -463,7 +464,16 @@ __global__ void __launch_bounds__(NW * 64, (8 * PA * PB / NW) >= 4 ? 2 : 4) bsmm
   // wave's tile is rounded to bf16 into a wave-private LDS staging tile (128-byte rows, chunk-swizzled like a
   // KC slab), kEpRows rows at a time, and written out as whole 128-byte row segments, 1 KB per store instruction.
   // `ep`: this wave's staging tile (kEpBytes; the accumulating form of the weight gradients uses 4 KB per 32 rows).
+  const int lane_of_thread = lane;
   auto epilogue = [&](const TileState& t, char* ep) {
+    // In a loop over items the per-lane addresses below would be computed once, ahead of the loop, spilled (the K loop
+    // needs every register) and reloaded one by one between the stores, each reload waiting for every load and store
+    // issued before it.  A lane number counted afresh (and opaque to the compiler) keeps them inside the epilogue.
+    int lane = lane_of_thread;
+    if constexpr (kRing) {
+      lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+      asm volatile("" : "+v"(lane));
+    }
     bf16_t* out;
     size_t ldo;
     size_t blk = 0;
