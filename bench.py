@@ -35,14 +35,14 @@ HBM_BOUND = {"tiny", "xs"}
 # summaries under profiles/ (dmoe_<workload>_hbm_bytes.txt): FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB, the factors
 # being what the same counters read for a 1 GiB elementwise copy (--copy-calibration) in the same runs.
 MEASURED_TRAFFIC = {
-    ("xs", "dsdt"): 210096333, ("xs", "sdd"): 260350976, ("xs", "ddts"): 186823270,
-    ("xs", "dstd"): 186819994, ("xs", "dsd"): 208352666, ("xs", "sddt"): 260302643,
-    ("small_zipf1.0", "ddts"): 987207885, ("small_zipf1.0", "dstd"): 1006448026, ("small_zipf1.0", "sdd"): 681239142,
-    ("small_zipf1.0", "dsdt"): 806032589, ("small_zipf1.0", "dsd"): 871372595, ("small_zipf1.0", "sddt"): 687388467,
-    ("medium_zipf1.2_top2", "sdd"): 2524065178, ("medium_zipf1.2_top2", "ddts"): 2754489549, ("medium_zipf1.2_top2", "dstd"): 2764244787,
-    ("medium_zipf1.2_top2", "sddt"): 2785978982, ("medium_zipf1.2_top2", "dsdt"): 2632176640, ("medium_zipf1.2_top2", "dsd"): 2608725402,
-    ("large_expert_top2", "sdd"): 28711848755, ("large_expert_top2", "dsd"): 16043077427, ("large_expert_top2", "dsdt"): 15031072973,
-    ("large_expert_top2", "sddt"): 29492886323, ("large_expert_top2", "dstd"): 13472427827, ("large_expert_top2", "ddts"): 15239494042,
+    ("xs", "dsdt"): 210515149, ("xs", "sdd"): 260303667, ("xs", "ddts"): 186822042,
+    ("xs", "dstd"): 186810778, ("xs", "dsd"): 207908864, ("xs", "sddt"): 260336640,
+    ("small_zipf1.0", "ddts"): 988802662, ("small_zipf1.0", "dstd"): 1011044557, ("small_zipf1.0", "dsdt"): 777336422,
+    ("small_zipf1.0", "sdd"): 639211315, ("small_zipf1.0", "dsd"): 874702029, ("small_zipf1.0", "sddt"): 639066931,
+    ("medium_zipf1.2_top2", "sdd"): 2429830144, ("medium_zipf1.2_top2", "ddts"): 2759092634, ("medium_zipf1.2_top2", "dstd"): 2761476096,
+    ("medium_zipf1.2_top2", "sddt"): 2585897779, ("medium_zipf1.2_top2", "dsdt"): 2617261875, ("medium_zipf1.2_top2", "dsd"): 2576706970,
+    ("large_expert_top2", "sdd"): 24057967411, ("large_expert_top2", "dsd"): 16102725018, ("large_expert_top2", "dsdt"): 15117702144,
+    ("large_expert_top2", "dstd"): 13325429146, ("large_expert_top2", "sddt"): 27807969894, ("large_expert_top2", "ddts"): 13869480960,
 }
 
 
