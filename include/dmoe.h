@@ -101,8 +101,8 @@ typedef struct {
                                             outlast a balanced schedule), else 0; sched[1] = tiles per XCD patch
                                             for those products (16 when no expert is large against an XCD's
                                             share of the rows, else 1); sched[2] = 1 if DSD / DSD^T, when launched
-                                            in both tile shapes, should take the single 128x128 blocks (the macro
-                                            tiles would leave more than 15 % of their last round of CUs empty);
+                                            in both tile shapes, should take the single 128x128 blocks (their
+                                            rounds of 512 come to less time than the macro tiles' rounds of 256);
                                             sched[3] reserved                                                    */
 } dmoe_topology_t;
 

@@ -1014,15 +1014,17 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
   const int big_minor = sparse_out ? (hb + 1) / 2 : (db + 1) / 2;
   if constexpr (row_major) {
     const long long big_items = (long long)a.groups_est * big_minor;
-    bool small = big_items < 256 + (sparse_out ? 1 : 0);
+    // SDD / SDD^T: macro tiles once there is one for every CU.  DSD / DSD^T (long K, few tiles): single blocks while
+    // they fit one round of 512 workgroup slots (128 macro tiles' worth); beyond that the device decides (below).
+    bool small = sparse_out ? big_items <= 256 : big_items <= 128;
     // DSD / DSD^T have a long K (= ffn_hidden) and few tiles; with fewer than about two and a half rounds of macro
     // tiles the last, partly filled round can cost up to half the launch (312 tiles on 256 CUs: 62 % of the CUs busy
     // on average), and how many tiles there are depends on the routing, which the host does not know.  The single
-    // blocks deliver the same flops per CU in steady state (two workgroups per CU) and are dispatched as CUs free up,
-    // so their tail is short -- DSD^T 286 -> 211 us for 16 384 tokens over 64 experts under Zipf routing -- but they
-    // lose 15 % when the macro tiles happen to fill their rounds exactly (uniform routing).  So in that range both
-    // shapes are launched and a flag computed on the device with the routing in hand (sched[2], offsets_kernel) picks
-    // one; the other exits at once (a few microseconds).
+    // blocks come in rounds of 512 (two workgroups per CU) that take about 1.0 us per K tile against the 1.6 us of a
+    // macro tile's, four blocks large: they win when their rounds are fewer than 1.6 x the macro tiles' -- DSD^T
+    // 286 -> 211 us for 16 384 tokens over 64 experts under Zipf routing (312 macro tiles) -- and lose otherwise (192
+    // macro tiles: 194 us against 160; 512: +15 %).  So in that range both shapes are launched and a flag computed on
+    // the device with the routing in hand (sched[2], offsets_kernel) picks one; the other exits at once.
     bool few_rounds = !sparse_out && !small && !a.plain && big_items < 640;
     if (a.force_tile == 1) small = true;
     if (a.force_tile >= 2) small = false;

@@ -339,11 +339,12 @@ __global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __res
     // eight XCDs cost 20 % on the skewed 64-expert configuration).  Otherwise the tiles are dealt out one by one,
     // heaviest expert first.
     sched[1] = (!heavy && 16LL * max_rows <= P / kBlock) ? 16 : 1;
-    // DSD / DSD^T when the host launched them in both tile shapes: take the single blocks when the macro tiles (row
-    // groups x pairs of d-blocks) would leave more than 15 % of their last round of 256 empty
+    // DSD / DSD^T when the host launched them in both tile shapes: the macro tiles (row groups x pairs of d-blocks) run
+    // in rounds of 256 at about 1.6 us per K tile, the single blocks (four per macro tile) in rounds of 512 at about
+    // 1.0 us; take whichever needs less time
     const long long big_items = (long long)gscan_s[E - 1] * ((db + 1) / 2);
-    const long long rounds = (big_items + 255) / 256;
-    sched[2] = (rounds > 0 && 100 * (rounds * 256 - big_items) > 15 * rounds * 256) ? 1 : 0;
+    const long long rounds_macro = (big_items + 255) / 256, rounds_single = (big_items + 127) / 128;
+    sched[2] = 10 * rounds_single < 16 * rounds_macro ? 1 : 0;
     sched[3] = 0;
   }
   if (tid < E) {                                           // position of expert `tid` in descending-load order
