@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--models", default="xs,small,medium")
     ap.add_argument("--no-vendor", action="store_true", help="skip the rocBLAS child process (block-sparse side only)")
+    ap.add_argument("--tile-mode", type=int, default=0, choices=(0, 1, 2, 3),
+                    help="0: the library's own tile choice (default); 1 / 2 / 3: forced tile shapes, as in bench.py")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="REFUSED.  Timing torch.bmm inside this process, after the library's steps, once ended in a GPU "
                          "memory fault reported by the synchronize after the torch.bmm loop; its cause was never "
@@ -80,6 +82,8 @@ def main():
 
     import torch
     import paper_2211_15841_amd as dm
+    if args.tile_mode:
+        dm.dmoe_set_tile_mode(args.tile_mode)
     from bench import HipEvents
     assert torch.cuda.is_available(), "needs a GPU"
     torch.cuda.set_device(0)
