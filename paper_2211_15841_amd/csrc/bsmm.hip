@@ -1015,16 +1015,18 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
   if constexpr (row_major) {
     const long long big_items = (long long)a.groups_est * big_minor;
     // SDD / SDD^T: macro tiles once there is one for every CU.  DSD / DSD^T (long K, few tiles): single blocks while
-    // they fit one round of 512 workgroup slots (128 macro tiles' worth); beyond that the device decides (below).
-    bool small = sparse_out ? big_items <= 256 : big_items <= 128;
+    // they are sure to fit one round of 512 workgroup slots whatever the routing (r_max bounds the block rows); beyond
+    // that the device decides (below) -- one block row too many doubles the rounds, and the time, of the single blocks.
+    bool small = sparse_out ? big_items <= 256 : (long long)a.r_max * db <= 512;
     // DSD / DSD^T have a long K (= ffn_hidden) and few tiles; with fewer than about two and a half rounds of macro
     // tiles the last, partly filled round can cost up to half the launch (312 tiles on 256 CUs: 62 % of the CUs busy
     // on average), and how many tiles there are depends on the routing, which the host does not know.  The single
     // blocks come in rounds of 512 (two workgroups per CU) that take about 1.0 us per K tile against the 1.6 us of a
     // macro tile's, four blocks large: they win when their rounds are fewer than 1.6 x the macro tiles' -- DSD^T
     // 286 -> 211 us for 16 384 tokens over 64 experts under Zipf routing (312 macro tiles) -- and lose otherwise (192
-    // macro tiles: 194 us against 160; 512: +15 %).  So in that range both shapes are launched and a flag computed on
-    // the device with the routing in hand (sched[2], offsets_kernel) picks one; the other exits at once.
+    // macro tiles: 194 us against 160; 512: +15 %; 8 192 tokens over 8 experts at d = 1 024, where 68 block rows make
+    // 544 single blocks: 139 us against 104).  So in that range both shapes are launched and a flag computed on the
+    // device with the routing in hand (sched[2], offsets_kernel) picks one; the other exits at once.
     bool few_rounds = !sparse_out && !small && !a.plain && big_items < 640;
     if (a.force_tile == 1) small = true;
     if (a.force_tile >= 2) small = false;
@@ -1042,7 +1044,8 @@ static void launch_one(const BsParams& p, const BsArgs& a, hipStream_t s) {
       // 128x256 tiles for DSD when the rows are few but the output is wide enough for every other CU to get one: the
       // block of A is then read once per two output blocks and W2 in 512-byte row pieces (-12 % on this product for
       // 8 192 tokens over 64 experts at d = 512; the other three token-row products did not gain)
-      if (small && !a.plain && 2LL * a.groups_est * big_minor >= 128 && db >= 2) {
+      // (one workgroup per CU: only while its tiles are sure to fit one round)
+      if (small && !a.plain && 2LL * a.groups_est * big_minor >= 128 && db >= 2 && (long long)a.r_max * big_minor <= 256) {
         launch_variant<OP, 1, 2, 2, 8>(p, a.r_max, big_minor, s);
         return;
       }

@@ -343,7 +343,7 @@ __global__ void __launch_bounds__(kOffsetsThreads) offsets_kernel(int32_t* __res
     // in rounds of 256 at about 1.6 us per K tile, the single blocks (four per macro tile) in rounds of 512 at about
     // 1.0 us; take whichever needs less time
     const long long big_items = (long long)gscan_s[E - 1] * ((db + 1) / 2);
-    const long long rounds_macro = (big_items + 255) / 256, rounds_single = (big_items + 127) / 128;
+    const long long rounds_macro = (big_items + 255) / 256, rounds_single = ((long long)(P / kBlock) * db + 511) / 512;
     sched[2] = 10 * rounds_single < 16 * rounds_macro ? 1 : 0;
     sched[3] = 0;
   }
