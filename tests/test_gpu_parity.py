@@ -68,6 +68,24 @@ def test_forced_expert_loads(counts):
     assert np.array_equal(gpu["topo"]["expert_idx"][:, 0], assignment)
 
 
+@pytest.mark.parametrize("counts,single", [
+    ([264] * 8, 0),                    # 24 block rows x 22 d-blocks: two rounds of single blocks, one of macro tiles
+    ([2112] + [0] * 7, 1),             # 17 block rows: one round either way, the single blocks are quicker
+], ids=["macro_tiles", "single_blocks"])
+def test_dsd_tile_shape_is_chosen_on_the_device(counts, single):
+    """DSD / DSD^T are launched in both tile shapes when the worst-case number of single blocks exceeds one round of 512
+    (here the bound is 24 block rows x 22); the device-side flag then picks one from the actual counts, and either choice
+    gives the oracle's results."""
+    E = len(counts)
+    assignment = np.repeat(np.arange(E), counts)
+    assignment = assignment[np.random.default_rng(5).permutation(len(assignment))]
+    cfg = small_config("dual", T=len(assignment), d=2816, h=256, E=E, k=1, seed=131)
+    inp = _forced_routing(cfg, assignment)
+    errs, gpu, ref = full_parity(cfg, inp)
+    assert ref["tokens_per_expert"].tolist() == counts
+    assert int(gpu["topo"]["sched"][2]) == single
+
+
 def test_forced_top2_with_ties_broken_by_lowest_index():
     T, E = 400, 8
     rng = np.random.default_rng(5)
